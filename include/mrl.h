@@ -1,0 +1,210 @@
+/*
+ * mrl.h - C ABI of the MI355X (gfx950) GRPO scoring library.
+ *
+ * The library computes the data-parallel hot path of a GRPO-based training
+ * step as used by the Mutual RL paper: per-token log-probabilities of the
+ * sampled tokens under the learner (LM-head projection, log-softmax over the
+ * full vocabulary, gather at the target id), group-relative advantages, the
+ * clipped importance-ratio surrogate with a KL term to a reference policy,
+ * and the backward pass to the hidden states and the LM-head weight.
+ *
+ * Conventions for every entry point
+ *   - Returns an mrl_status (0 = MRL_OK, negative = error).  Never throws,
+ *     never aborts.  Arguments are validated on the host before any device
+ *     work is enqueued; on error nothing has been launched.
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The
+ *     library allocates no device memory: scratch space comes from the
+ *     caller's workspace, whose size is obtained from the matching
+ *     *_workspace() query (256-byte aligned base required).
+ *   - Work is enqueued on the caller's stream (a hipStream_t passed as
+ *     void*, NULL = the default stream) and is asynchronous: outputs are
+ *     valid once the caller has synchronised that stream.  No host
+ *     synchronisation happens inside a call.
+ *   - Inputs are never modified.  Outputs are fully overwritten, except
+ *     out_dW when accumulate_dw = 1.
+ *   - All tensors are dense and row-major.  lm_head_w is [V, d], one row per
+ *     vocabulary id (the layout of a linear layer's weight).  Row n of hidden
+ *     is the final hidden state that PREDICTS target_ids[n]; the shift
+ *     between inputs and labels is the caller's business.  No bias, sampling
+ *     temperature 1.
+ *   - dtype MRL_BF16: hidden / lm_head_w are bfloat16, matrix products run on
+ *     the bf16 MFMA units with fp32 accumulation; d must be a multiple of 64.
+ *     dtype MRL_F32: hidden / lm_head_w are float, plain fp32 arithmetic (a
+ *     small-shape sanity path, not tuned); any d >= 1.
+ *   - Only gfx950 devices are supported; there is no fallback path.
+ */
+#ifndef MRL_H
+#define MRL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MRL_OK = 0,
+  MRL_ERR_NULL = -1,             /* a required pointer is NULL                          */
+  MRL_ERR_SHAPE = -2,            /* a size is <= 0, too large, or violates a divisibility rule */
+  MRL_ERR_DTYPE = -3,            /* unknown mrl_dtype                                   */
+  MRL_ERR_TARGET_RANGE = -4,     /* reserved: target ids are checked on the device (see stats) */
+  MRL_ERR_GROUP_RANGE = -5,      /* reserved: group ids are checked on the device       */
+  MRL_ERR_WORKSPACE = -6,        /* workspace NULL, misaligned or too small             */
+  MRL_ERR_CONFIG = -7,           /* a configuration value is out of its domain          */
+  MRL_ERR_DEVICE = -8,           /* no usable device / a HIP call failed                */
+  MRL_ERR_UNSUPPORTED_ARCH = -9  /* the current device is not gfx950                    */
+} mrl_status;
+
+typedef enum { MRL_F32 = 0, MRL_BF16 = 1 } mrl_dtype;
+
+typedef enum {
+  MRL_ADV_CENTER = 0,   /* A = r - mean(group)                     (Sec. 3, A-tilde)            */
+  MRL_ADV_GROUP_ZN = 1, /* A = (r - mean) / (std(group) + eps)     (Sec. 3, A-tilde-zn)         */
+  MRL_ADV_BATCH_ZN = 2  /* centre per group, divide by the std over all scored entries (App. A) */
+} mrl_adv_mode;
+
+/* bits of out_flags[g] of mrl_group_advantages (SGT gate, Sec. 5.3 / App. B) */
+#define MRL_FLAG_ALL_FAIL 1u     /* every own rollout of the group has reward < neg_thresh */
+#define MRL_FLAG_PEER_SUCCESS 2u /* some non-own entry has reward > pos_thresh             */
+#define MRL_FLAG_RESCUE 4u       /* both: the gate fires for this prompt                   */
+
+const char* mrl_status_string(int status);
+int mrl_version(void);
+
+/* ------------------------------------------------------------------------
+ * (1) Token log-probabilities  l_theta[n] = log pi_theta(y_n | context)
+ *     (Sec. 3, GRPO paragraph: the entries of the trace l_theta(x, y)).
+ *
+ *   z[n, v] = sum_k hidden[n, k] * lm_head_w[v, k]
+ *   lse[n]  = log sum_v exp z[n, v]
+ *   out_logp[n] = z[n, target_ids[n]] - lse[n]
+ *
+ * The N x V logits are never written to memory.  token_mask (uint8, 0/1) may
+ * be NULL (= every row is scored); rows with mask 0 or with a target id
+ * outside [0, V) are skipped and report out_logp = out_lse = 0.  out_lse may
+ * be NULL.  N >= 0 (N = 0 is a no-op).
+ * ---------------------------------------------------------------------- */
+size_t mrl_token_logprobs_workspace(int64_t N, int32_t d, int32_t V, int32_t dtype);
+int mrl_token_logprobs(const void* hidden /*[N,d] dev*/, const void* lm_head_w /*[V,d] dev*/,
+                       const int32_t* target_ids /*[N] dev*/,
+                       const uint8_t* token_mask /*[N] dev | NULL*/,
+                       int64_t N, int32_t d, int32_t V, int32_t dtype,
+                       float* out_logp /*[N] dev*/, float* out_lse /*[N] dev | NULL*/,
+                       void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * (2) Group-relative advantages and the SGT gate.
+ *     Sec. 3: rbar = mean of the group's rewards, A~ = r - rbar,
+ *     A~zn = A~ / (std + eps).  Sec. 5.1 (PRP): own and peer rollouts of a
+ *     prompt form one group and are normalised together.  App. G.1 (XGRPO):
+ *     the baseline mean / std pool the rewards of every policy while only
+ *     own rollouts are scored.  Sec. 5.3 / App. B (SGT): the gate fires for a
+ *     prompt when every own rollout failed and some peer succeeded.
+ *
+ * Entries b = 0..B-1 are rollouts (or bare peer rewards); group_id[b] in
+ * [0, G) names the prompt; entries of a group need not be contiguous.
+ *   in_stats[b] = 1 : the reward enters the group's mean / std   (NULL = all 1)
+ *   scored[b]   = 1 : an advantage is emitted, else out_adv[b] = 0 (NULL = all 1)
+ *   is_own[b]   = 1 : the rollout is the learner's own             (NULL = all 1)
+ * std uses divisor (count - ddof), ddof in {0, 1}; std = 0 if count <= ddof.
+ * mix_alpha in [0, 1]: A = (1 - alpha) * A_own + alpha * A_pool, where A_own
+ * uses statistics over (in_stats & is_own) entries only; 1 = pooled rule.
+ * An entry whose group id is outside [0, G) gets advantage 0 and enters no
+ * statistic.  Sums are accumulated in fp64 in a fixed order (bit-reproducible).
+ * Optional outputs (NULL to skip): out_group_mean / out_group_std (pooled
+ * statistics), out_flags (MRL_FLAG_* bits).
+ * ---------------------------------------------------------------------- */
+int mrl_group_advantages(const float* rewards /*[B] dev*/, const int32_t* group_id /*[B] dev*/,
+                         const uint8_t* in_stats /*[B] dev | NULL*/,
+                         const uint8_t* scored /*[B] dev | NULL*/,
+                         const uint8_t* is_own /*[B] dev | NULL*/,
+                         int64_t B, int32_t G, int32_t adv_mode, float eps_norm, int32_t ddof,
+                         float mix_alpha, float neg_thresh, float pos_thresh,
+                         float* out_adv /*[B] dev*/, float* out_group_mean /*[G] dev | NULL*/,
+                         float* out_group_std /*[G] dev | NULL*/, uint8_t* out_flags /*[G] dev | NULL*/,
+                         void* stream);
+
+/* ------------------------------------------------------------------------
+ * (3) Fused scoring + GRPO loss, forward and backward.
+ *     Eq. (1): L_GRPO = - E_x (1/K) sum_i E_tok[ min(w A, clip(w, 1-eps, 1+eps) A) ]
+ *              + beta * R(theta),  w = exp(l_theta - l_behaviour);
+ *     R(theta) is the k3 estimator exp(rho) - rho - 1, rho = l_ref - l_theta,
+ *     averaged with the same weights.  Eq. (2): auxiliary SGT rows add
+ *     lambda * (- token-mean l_theta), averaged over the auxiliary rows.
+ *     behav_logp carries l_old for own rollouts and the aligned peer trace
+ *     for pooled peer rollouts (Sec. 5.1, the two denominators); advantages,
+ *     behaviour and reference traces are constants of the differentiation.
+ *
+ * Tokens are [B, T] right- or arbitrarily padded, token_mask marks scored
+ * slots.  seq_kind[b]: 0 = GRPO row, 1 = SGT auxiliary row (NULL = all 0).
+ * Weights (loss_agg = 0): c = mask / (P * K_g * L_b) for GRPO rows, with L_b
+ * the row's scored tokens, K_g the GRPO rows of its group, P the groups with
+ * a GRPO row; c_sgt = mask / (S_aux * L_b), S_aux = auxiliary rows with
+ * L_b > 0.  loss_agg = 1: c = mask / (all scored GRPO tokens).
+ * Backward: g = dL/dl; dz[n, v] = g[n] (1[v = y_n] - softmax[n, v]);
+ * out_dH = dz W (rows of unscored slots are zero), out_dW (+)= dz^T H in fp32.
+ * out_dH and/or out_dW may be NULL to skip that gradient.
+ * ref_logp may be NULL when kl_beta = 0.  group_id[b] must lie in [0, G); a
+ * row with an id outside gets weight 0.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  float clip_eps_low;    /* lower clip: ratios below 1 - clip_eps_low are clipped; paper: 0.2 */
+  float clip_eps_high;   /* upper clip: 1 + clip_eps_high; paper: 0.2                         */
+  float kl_beta;         /* coefficient of the KL term (paper's runs: 1e-3)                   */
+  float sgt_lambda;      /* weight of the SGT auxiliary loss (paper: 0.1)                     */
+  int32_t loss_agg;      /* 0 = Eq. (1) literal (seq-mean of token-means), 1 = global token mean */
+  int32_t accumulate_dw; /* 0 = overwrite out_dW, 1 = add into it                             */
+  int32_t dh_dtype;      /* mrl_dtype of out_dH                                               */
+  int32_t chunk_rows;    /* 0 = automatic; else scored rows per pass (multiple of 256)        */
+} mrl_loss_config;
+
+typedef struct {
+  double loss_total, loss_pg, loss_kl, loss_sgt; /* L = pg + beta*kl + lambda*sgt */
+  double mean_ratio, max_ratio, mean_k3;         /* over scored GRPO tokens       */
+  int64_t n_scored_tokens;                       /* scored slots with a valid target */
+  int64_t n_clipped_tokens;                      /* ratio outside [1-eps_low, 1+eps_high] */
+  int64_t n_zero_grad_tokens;                    /* clipped branch active (no surrogate gradient) */
+  int64_t n_bad_targets;                         /* masked-in slots whose target id is outside [0,V) */
+} mrl_loss_stats;
+
+size_t mrl_grpo_loss_workspace(int64_t B, int32_t T, int32_t d, int32_t V, int32_t dtype,
+                               const mrl_loss_config* cfg);
+int mrl_grpo_loss_fwd_bwd(const void* hidden /*[B*T,d] dev*/, const void* lm_head_w /*[V,d] dev*/,
+                          const int32_t* target_ids /*[B*T] dev*/,
+                          const uint8_t* token_mask /*[B*T] dev*/,
+                          const float* behav_logp /*[B*T] dev*/,
+                          const float* ref_logp /*[B*T] dev | NULL*/,
+                          const float* seq_adv /*[B] dev*/, const int32_t* group_id /*[B] dev*/,
+                          const uint8_t* seq_kind /*[B] dev | NULL*/,
+                          int64_t B, int32_t T, int32_t G, int32_t d, int32_t V, int32_t dtype,
+                          const mrl_loss_config* cfg /*host*/,
+                          float* out_logp /*[B*T] dev*/, void* out_dH /*[B*T,d] dev | NULL*/,
+                          float* out_dW /*[V,d] dev | NULL*/, mrl_loss_stats* out_stats /*dev*/,
+                          void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Per-kernel-class timing for benchmarks.  When enabled, every kernel launch
+ * of the calls above is bracketed by HIP events on the launch stream.
+ * mrl_profile_collect synchronises the device, adds up the elapsed time and
+ * launch count per class since the last collect, and resets the log.
+ * Arrays are HOST memory of MRL_PROF_NCLASS entries.
+ * ---------------------------------------------------------------------- */
+enum {
+  MRL_PROF_PREP = 0,      /* mask scan, compaction, sequence weights, zero fill */
+  MRL_PROF_ADV = 1,       /* group advantages */
+  MRL_PROF_GEMM_FWD = 2,  /* logits tile GEMM with fused log-sum-exp */
+  MRL_PROF_ROW_EPI = 3,   /* partial merge, ratio / clip / KL, loss partials */
+  MRL_PROF_CONVERT = 4,   /* logits -> dz conversion and operand transposes */
+  MRL_PROF_GEMM_DH = 5,   /* dH = dz W */
+  MRL_PROF_GEMM_DW = 6,   /* dW += dz^T H */
+  MRL_PROF_FINAL = 7,     /* final reductions */
+  MRL_PROF_NCLASS = 8
+};
+int mrl_profile_enable(int on);
+int mrl_profile_collect(double* ms_per_class /*host*/, int64_t* launches_per_class /*host*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MRL_H */

@@ -1,0 +1,136 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mrl {
+
+// Column padding of the per-chunk logit / dz buffers: the vocabulary is padded
+// to a multiple of the GEMM tile so that inner kernels never see a ragged K.
+constexpr int kTile = 256;
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Number of (max, sum-exp) partials each token row receives from the forward
+// kernel: the bf16 kernel emits two per 256-wide vocabulary tile (one per wave
+// row), the fp32 path a single one per row.
+inline int fwd_partials_bf16(int V) { return 2 * (int)((V + kTile - 1) / kTile); }
+
+// ---- bf16 MFMA GEMM family: C[m][n] = sum_k A[m][k] * B[n][k] ---------------
+// n_scored: device pointer to the number of compacted rows; chunk_start/chunk_rows
+// select the rows this launch covers (valid rows = clamp(n_scored - chunk_start, 0, chunk_rows)).
+
+// Forward: A = W [V, d], B = H rows gathered through row_index[chunk_start + n].
+// Writes per-row partials part_max/part_sum[(2*tile_m + wave_m) * chunk_rows + n]
+// and, when zstash != nullptr, the logits as fp16 into zstash[n * ldz + v].
+void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index,
+                          const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
+                          int V, int d, float* part_max, float* part_sum,
+                          void* zstash, int64_t ldz, hipStream_t stream);
+
+// dH: A = P [chunk_rows, Vp] (bf16 dz), B = Wt [d, Vp]; row m goes to
+// dH[row_index[chunk_start + m], :] as bf16 (dh_f32 = 0) or float (dh_f32 = 1).
+void launch_gemm_dh_bf16(const void* P, int64_t ldp, const void* Wt, int64_t ldwt,
+                         const int32_t* row_index, const int64_t* n_scored, int64_t chunk_start,
+                         int chunk_rows, int Vp, int d, void* dH, int dh_f32, hipStream_t stream);
+
+// dW: A = Pt [Vp, chunk_rows], B = Ht [d, chunk_rows]; dW[v, :] = (or +=) sum over the
+// chunk's valid rows.  overwrite = 1 stores, 0 adds into the existing values.
+void launch_gemm_dw_bf16(const void* Pt, int64_t ldpt, const void* Ht, int64_t ldht,
+                         const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
+                         int V, int d, float* dW, int overwrite, hipStream_t stream);
+
+// ---- fp32 plain GEMM (sanity path): C[m][n] = sum_k A[m][k] * B[n][k] --------
+// a_rows / c_rows: optional row maps (index arrays already offset to the chunk);
+// m_valid is computed on the device from n_scored when m_dynamic != 0, and
+// k_valid likewise when k_dynamic != 0.
+struct GemmF32Args {
+  const float* A; int64_t lda; const int32_t* a_rows;
+  const float* B; int64_t ldb;
+  float* C; int64_t ldc; const int32_t* c_rows;
+  int M, N, K;
+  const int64_t* n_scored; int64_t chunk_start; int chunk_rows;
+  int m_dynamic, k_dynamic;
+  int accumulate;
+};
+void launch_gemm_f32(const GemmF32Args& a, hipStream_t stream);
+
+// ---- auxiliary kernels ------------------------------------------------------
+struct PrepOut {
+  int32_t* row_index;   // [N] compacted scored slots, in slot order; tail filled with 0
+  int64_t* n_scored;    // [1]
+  int64_t* n_bad;       // [1] masked-in slots with a target outside [0, V)
+  int32_t* block_counts; // scratch [ceil(N / 1024) + 1]
+};
+void launch_prep(const uint8_t* mask, const int32_t* targets, int64_t N, int V, const PrepOut& o,
+                 hipStream_t stream);
+
+// Per-sequence scored length (valid targets only) and loss weights.
+// seq_coef[b] = 1 / (P K_g L_b) for GRPO rows, lambda / (S_aux L_b) for SGT rows
+// (sign and lambda folded so that g = seq_coef * (...)), 0 for empty rows.
+void launch_seq_weights(const uint8_t* mask, const int32_t* targets, const int32_t* group_id,
+                        const uint8_t* seq_kind, int64_t B, int T, int G, int V, int loss_agg,
+                        int32_t* seq_len, float* seq_coef, int32_t* group_count /*[G] scratch*/,
+                        hipStream_t stream);
+
+// Zero out_logp (and out_lse, dH rows) of unscored slots.
+void launch_zero_unscored(const uint8_t* mask, const int32_t* targets, int64_t N, int V, int d,
+                          float* out_logp, float* out_lse, void* dH, int dh_elem_bytes,
+                          hipStream_t stream);
+
+// Target logit z_t[i] = <H[row_index[i]], W[target]> for compacted rows (fp32 accumulate).
+void launch_target_logit(const void* H, const void* W, const int32_t* targets,
+                         const int32_t* row_index, const int64_t* n_scored, int64_t N_max,
+                         int d, int is_bf16, float* zt, hipStream_t stream);
+
+// fp32 path: (max, sum-exp) of each row of Z [rows, V] -> one partial per row.
+void launch_row_lse_f32(const float* Z, int64_t ldz, const int64_t* n_scored, int64_t chunk_start,
+                        int chunk_rows, int V, float* part_max, float* part_sum, hipStream_t stream);
+
+struct RowEpiArgs {
+  const float* part_max; const float* part_sum; int n_partials; int chunk_rows;
+  const float* zt;            // [N] compacted
+  const int32_t* row_index; const int64_t* n_scored; int64_t chunk_start;
+  // loss inputs (all nullptr for the log-prob-only entry point)
+  const float* behav_logp; const float* ref_logp; const float* seq_adv;
+  const float* seq_coef; const uint8_t* seq_kind; int T;
+  float eps_lo, eps_hi, beta, lambda;
+  float* out_logp; float* out_lse;  // per slot
+  float* lse_c; float* g_c;         // per compacted row (nullptr to skip)
+  double* loss_partials;            // [n_blocks_total][8], block index = chunk block offset + blockIdx
+  int64_t partial_block_offset;
+};
+int row_epilogue_blocks(int chunk_rows);
+void launch_row_epilogue(const RowEpiArgs& a, hipStream_t stream);
+
+// dz conversion: reads the chunk's logits (fp16 for the bf16 path, float for fp32),
+// writes P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)) in place (same element size)
+// and the transpose Pt[v][i]; rows >= valid rows and columns >= V become zero.
+void launch_convert(void* ZP, int64_t ldz, void* Pt, int64_t ldpt, const float* lse_c,
+                    const float* g_c, const int32_t* targets, const int32_t* row_index,
+                    const int64_t* n_scored, int64_t chunk_start, int chunk_rows, int V, int Vp,
+                    int is_bf16, hipStream_t stream);
+
+// Out[c][r] = In[rows[r]][c] (rows == nullptr: identity) for r < n_rows_valid, zero beyond,
+// r in [0, out_cols_pad), c in [0, n_cols).  Used for Wt (static) and Ht (gathered, dynamic).
+void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, void* out, int64_t ld_out,
+                      int64_t n_rows_static, const int64_t* n_scored, int64_t chunk_start,
+                      int chunk_rows, int n_cols, int64_t out_cols_pad, int elem_bytes,
+                      hipStream_t stream);
+
+// Group-relative advantages (Sec. 3) with pooled / own statistics and SGT gate flags.
+void launch_group_advantages(const float* rewards, const int32_t* group_id, const uint8_t* in_stats,
+                             const uint8_t* scored, const uint8_t* is_own, int64_t B, int G,
+                             int mode, float eps_norm, int ddof, float mix_alpha, float neg_thresh,
+                             float pos_thresh, float* out_adv, float* out_mean, float* out_std,
+                             uint8_t* out_flags, hipStream_t stream);
+
+void launch_finalize(const double* loss_partials, int64_t n_blocks, const int64_t* n_scored,
+                     const int64_t* n_bad, float beta, float lambda, void* out_stats,
+                     hipStream_t stream);
+
+// ---- profiling ---------------------------------------------------------------
+void prof_begin(int cls, hipStream_t stream);
+void prof_end(int cls, hipStream_t stream);
+
+}  // namespace mrl

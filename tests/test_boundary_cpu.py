@@ -1,0 +1,135 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol declared in include/mrl.h, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_07244_amd as m
+from paper_2605_07244_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mrl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mrl_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = m.lib()
+    names = _declared_symbols()
+    assert {"mrl_token_logprobs", "mrl_group_advantages", "mrl_grpo_loss_fwd_bwd"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings():
+    assert m.version() >= 100
+    assert m.status_string(0) == "ok"
+    for code in range(-9, 0):
+        assert m.status_string(code) not in ("ok", "unknown status")
+    assert m.status_string(-99) == "unknown status"
+
+
+def test_stats_struct_size_matches_header():
+    # 7 doubles + 4 int64 (see mrl_loss_stats)
+    assert binding.STATS_BYTES == 88 and len(binding.STATS_FIELDS) == 11
+
+
+P = ctypes.c_void_p
+FAKE = P(0x1000)   # never dereferenced: validation fails first
+
+
+def _cfg(**kw):
+    return binding.LossConfig(**kw).to_c()
+
+
+def test_token_logprobs_argument_errors():
+    lib = m.lib()
+    f = lib.mrl_token_logprobs
+    assert f(None, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -1
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, None, None, FAKE, 1 << 20, None) == -1
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 7, FAKE, None, FAKE, 1 << 20, None) == -3
+    assert f(FAKE, FAKE, FAKE, None, -1, 64, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2
+    assert f(FAKE, FAKE, FAKE, None, 8, 0, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 0, 1, FAKE, None, FAKE, 1 << 20, None) == -2
+    assert f(FAKE, FAKE, FAKE, None, 8, 72, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2   # bf16: d % 64
+    assert f(FAKE, FAKE, FAKE, None, 0, 64, 32, 1, FAKE, None, None, 0, None) == 0          # N = 0: no-op
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, None, 0, None) == -6
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, P(0x1001), 1 << 20, None) == -6  # misaligned
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, FAKE, 16, None) == -6           # too small
+
+
+def test_workspace_queries():
+    assert m.token_logprobs_workspace(1024, 128, 1000, m.BF16) > 0
+    assert m.token_logprobs_workspace(1024, 100, 1000, m.BF16) == 0      # invalid shape -> 0
+    small = m.grpo_loss_workspace(4, 64, 128, 1000, m.BF16, m.LossConfig(chunk_rows=256))
+    big = m.grpo_loss_workspace(4, 64, 128, 1000, m.BF16, m.LossConfig(chunk_rows=1024))
+    assert 0 < small < big
+    assert m.grpo_loss_workspace(4, 64, 128, 1000, m.BF16, m.LossConfig(chunk_rows=100)) == 0
+    # the stress configuration fits comfortably into one GPU's HBM
+    ws5 = m.grpo_loss_workspace(1024, 2048, 4096, 151936, m.BF16, m.LossConfig())
+    assert 5e9 < ws5 < 40e9
+
+
+def test_group_advantages_argument_errors():
+    f = m.lib().mrl_group_advantages
+    ok_tail = (FAKE, None, None, None, None)
+    assert f(None, FAKE, None, None, None, 8, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -1
+    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, None, None, None, None, None) == -1
+    assert f(FAKE, FAKE, None, None, None, 8, 0, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -2
+    assert f(FAKE, FAKE, None, None, None, -1, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -2
+    assert f(FAKE, FAKE, None, None, None, 8, 2, 5, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, -1.0, 0, 1.0, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, 1e-6, 2, 1.0, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, 1e-6, 0, 1.5, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, 0, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == 0
+
+
+def _loss(cfg, *, hidden=FAKE, ref=FAKE, B=4, T=8, G=2, d=64, V=100, dt=1, ws=FAKE, ws_bytes=1 << 30,
+          stats=FAKE, seq_adv=FAKE):
+    f = m.lib().mrl_grpo_loss_fwd_bwd
+    return f(hidden, FAKE, FAKE, FAKE, FAKE, ref, seq_adv, FAKE, None, B, T, G, d, V, dt,
+             ctypes.byref(cfg) if cfg is not None else None, FAKE, FAKE, FAKE, stats, ws, ws_bytes, None)
+
+
+def test_loss_argument_errors():
+    good = _cfg()
+    assert _loss(good, hidden=None) == -1
+    assert _loss(good, stats=None) == -1
+    assert _loss(None) == -1
+    assert _loss(good, ref=None) == -1                       # beta > 0 needs a reference trace
+    assert _loss(good, B=0) == -2
+    assert _loss(good, T=0) == -2
+    assert _loss(good, G=0) == -2
+    assert _loss(good, G=9) == -2                            # more groups than sequences
+    assert _loss(good, d=65) == -2
+    assert _loss(good, dt=3) == -3
+    assert _loss(_cfg(clip_eps_low=-0.1)) == -7
+    assert _loss(_cfg(kl_beta=-1.0)) == -7
+    assert _loss(_cfg(loss_agg=2)) == -7
+    assert _loss(_cfg(accumulate_dw=3)) == -7
+    assert _loss(_cfg(dh_dtype=5)) == -7
+    assert _loss(_cfg(chunk_rows=300)) == -7
+    assert _loss(_cfg(dh_dtype=1), dt=0) == -7               # fp32 path writes fp32 dH only
+    assert _loss(good, ws=None) == -6
+    assert _loss(good, ws_bytes=1024) == -6
+
+
+def test_no_device_is_an_error_not_a_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    # all arguments valid: the call must stop at the device check, nothing is computed on the CPU
+    rc = _loss(_cfg())
+    assert rc in (-8, -9)
+
+
+def test_profile_calls_without_device():
+    assert m.lib().mrl_profile_enable(0) == 0
+    assert m.lib().mrl_profile_collect(None, None) == -1
+    out = m.profile_collect()
+    assert set(out) == set(m.PROF_CLASSES)
