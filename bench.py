@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the GRPO scoring hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic batch already
+resident in HBM: group advantages, then the fused LM-head + log-softmax + GRPO
+loss forward and backward (dH, dW).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--full-length]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "scored tokens/sec, fused LM-head+logsoftmax+GRPO fwd+bwd; % bf16 MFMA peak"
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def cpu_baseline(batch, sp, rows_T=256):
+    """Times the CPU oracle (as it stands) on a bounded sample of the same workload:
+    the first prompt's rollouts truncated to their first `rows_T` tokens, at full V and d."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import mrl_oracle as orc
+    from tests import util
+
+    T = batch["T"]
+    k = sp.k_own + sp.k_peer
+    t_sub = min(rows_T, T)
+    rows = (np.arange(k)[:, None] * T + np.arange(t_sub)[None, :]).reshape(-1)
+    import torch
+    ridx = torch.tensor(rows, device=batch["H"].device)
+    H = util.to_f64(batch["H"][ridx])
+    W = util.to_f64(batch["W"])
+    y = batch["targets"][ridx].cpu().numpy()
+    mask = batch["mask"].reshape(-1)[ridx].cpu().numpy().reshape(k, t_sub)
+    behav = util.to_f64(batch["behav"][ridx])
+    ref = util.to_f64(batch["ref"][ridx])
+    rewards = util.to_f64(batch["rewards_all"][:k])
+    gid = np.zeros(k, dtype=np.int64)
+    cfg = util.cfg_dict(sp)
+    t0 = time.perf_counter()
+    adv, *_ = orc.group_advantages(rewards, gid, 1)
+    out = orc.grpo_loss_fwd_bwd(H, W, y, mask, behav, ref, adv, gid, None, k, t_sub, 1, cfg)
+    dt = time.perf_counter() - t0
+    n_tok = int(mask.sum())
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    assert np.isfinite(out["loss_total"])
+    return dict(value=n_tok / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"{k} sequences x first {t_sub} tokens ({n_tok} scored rows) at full V={sp.V}, d={sp.d}; "
+                       f"fp64 NumPy, {dt:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration index (2..5)")
+    ap.add_argument("--full-length", action="store_true", help="score every slot (no padding)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-rows", type=int, default=0)
+    ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (debug)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1")
+
+    import torch
+
+    import paper_2605_07244_amd as mrl
+    from paper_2605_07244_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    mrl.lib()
+
+    over = {}
+    if args.full_length:
+        over["len_dist"] = "full"
+    if args.prompts:
+        over["n_prompts"] = args.prompts
+    sp = synth.spec(args.config, **over)
+    log(f"generating workload {sp.name}: V={sp.V} d={sp.d} prompts={sp.n_prompts} T={sp.T}")
+    batch = synth.make(sp, "cuda")
+    B, T, G, N, V, d = (batch[k] for k in ("B", "T", "G", "N", "V", "d"))
+    n_scored = int(batch["mask"].sum().item())
+    mask = batch["mask"].reshape(-1)
+    cfg = mrl.LossConfig(clip_eps_low=sp.clip_eps, clip_eps_high=sp.clip_eps, kl_beta=sp.kl_beta,
+                         sgt_lambda=sp.sgt_lambda, dh_dtype=mrl.BF16, chunk_rows=args.chunk_rows,
+                         scored_rows_hint=n_scored)
+    ws_bytes = mrl.grpo_loss_workspace(B, T, d, V, mrl.BF16, cfg)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    out_logp = torch.empty(N, dtype=torch.float32, device="cuda")
+    out_dH = torch.empty((N, d), dtype=torch.bfloat16, device="cuda")
+    out_dW = torch.empty((V, d), dtype=torch.float32, device="cuda")
+    out_stats = torch.empty(mrl.binding.STATS_BYTES, dtype=torch.uint8, device="cuda")
+    log(f"N={N} slots, {n_scored} scored, workspace {ws_bytes / 1e9:.2f} GB")
+
+    def step():
+        adv, _, _, _ = mrl.group_advantages(batch["rewards_all"], batch["group_all"], G, batch["in_stats"],
+                                            batch["scored"], batch["is_own"])
+        seq_adv = adv if adv.numel() == B else synth.seq_adv_from(adv, batch)
+        return mrl.grpo_loss_fwd_bwd(batch["H"], batch["W"], batch["targets"], mask, batch["behav"], batch["ref"],
+                                     seq_adv, batch["seq_group"], batch["seq_kind"], B, T, G, cfg,
+                                     out_dH=out_dH, out_dW=out_dW, workspace=ws, out_logp=out_logp,
+                                     out_stats=out_stats)
+
+    for i in range(args.warmup):
+        step()
+        torch.cuda.synchronize()
+        log(f"warmup {i + 1}/{args.warmup} done")
+    mrl.profile_enable(True)
+    mrl.profile_collect()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = mrl.profile_collect()
+    mrl.profile_enable(False)
+    stats = mrl.read_stats(out_stats)
+    assert stats["n_scored_tokens"] == n_scored and stats["n_unprocessed_rows"] == 0, stats
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = n_scored * args.steps / elapsed
+    flop_per_token = 6.0 * d * V
+    pct_peak = 100.0 * tokens_per_s * flop_per_token / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+
+    # roofline of the dominant kernel class: algorithmic flops of its launches / their duration
+    gemm = {k: prof[k] for k in ("gemm_fwd", "gemm_dh", "gemm_dw")}
+    dom = max(gemm, key=lambda k: gemm[k][0])
+    dom_ms, dom_launches = gemm[dom]
+    flops_per_launch = 2.0 * n_scored * d * V * args.steps / max(dom_launches, 1)
+    avg_launch_ms = dom_ms / max(dom_launches, 1)
+    achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12 if avg_launch_ms > 0 else 0.0
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get(f"{dom}:config{args.config}")
+        except Exception:
+            traffic = None
+    roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=MFMA_BF16_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), traffic=traffic,
+                    avg_launch_ms=round(avg_launch_ms, 3), launches=int(dom_launches),
+                    flops_per_launch=flops_per_launch)
+    classes = {k: dict(ms_per_step=round(v[0] / args.steps, 3), launches_per_step=v[1] / args.steps)
+               for k, v in prof.items()}
+
+    base = None
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample")
+        base = cpu_baseline(batch, sp)
+
+    line = dict(metric=METRIC, value=round(tokens_per_s, 1), unit="tokens/s", n_gpus=1, steps=args.steps,
+                warmup=args.warmup, ms_per_step=round(ms_per_step, 3), higher_is_better=True, scaling="weak",
+                vs_baseline=None, dtype="bf16", data="synthetic",
+                config=dict(workload=f"config{args.config}:{sp.name}" + (":full-length" if args.full_length else ""),
+                            V=V, d=d, B=B, T=T, slots=N, scored_tokens=n_scored, prompts=sp.n_prompts,
+                            rollouts_per_prompt=sp.k_own + sp.k_peer),
+                pct_bf16_mfma_peak=round(pct_peak, 2), flop_per_token=flop_per_token,
+                roofline=roofline, kernel_classes=classes, cpu_baseline=base,
+                loss=dict(total=stats["loss_total"], clip_frac=stats["n_clipped_tokens"] / max(n_scored, 1),
+                          mean_ratio=stats["mean_ratio"]))
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -157,6 +157,12 @@ typedef struct {
   int32_t accumulate_dw; /* 0 = overwrite out_dW, 1 = add into it                             */
   int32_t dh_dtype;      /* mrl_dtype of out_dH                                               */
   int32_t chunk_rows;    /* 0 = automatic; else scored rows per pass (multiple of 256)        */
+  int64_t scored_rows_hint; /* 0 = unknown.  Else an upper bound on the number of scored slots the
+                               caller vouches for (it usually knows the sequence lengths): only
+                               ceil(hint / chunk_rows) passes are enqueued instead of the worst case
+                               ceil(B*T / chunk_rows).  If the mask holds more scored slots than the
+                               hint, the excess rows are NOT processed: their out_logp is NaN and
+                               n_unprocessed_rows reports how many.                              */
 } mrl_loss_config;
 
 typedef struct {
@@ -166,6 +172,7 @@ typedef struct {
   int64_t n_clipped_tokens;                      /* ratio outside [1-eps_low, 1+eps_high] */
   int64_t n_zero_grad_tokens;                    /* clipped branch active (no surrogate gradient) */
   int64_t n_bad_targets;                         /* masked-in slots whose target id is outside [0,V) */
+  int64_t n_unprocessed_rows;                    /* scored slots beyond scored_rows_hint (0 unless the hint was wrong) */
 } mrl_loss_stats;
 
 size_t mrl_grpo_loss_workspace(int64_t B, int32_t T, int32_t d, int32_t V, int32_t dtype,

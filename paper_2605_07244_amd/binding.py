@@ -35,7 +35,7 @@ def library_path() -> str:
 class _LossConfig(ctypes.Structure):
     _fields_ = [("clip_eps_low", c_float), ("clip_eps_high", c_float), ("kl_beta", c_float),
                 ("sgt_lambda", c_float), ("loss_agg", c_int32), ("accumulate_dw", c_int32),
-                ("dh_dtype", c_int32), ("chunk_rows", c_int32)]
+                ("dh_dtype", c_int32), ("chunk_rows", c_int32), ("scored_rows_hint", c_int64)]
 
 
 @dataclass
@@ -48,15 +48,18 @@ class LossConfig:
     accumulate_dw: int = 0
     dh_dtype: int = BF16
     chunk_rows: int = 0
+    scored_rows_hint: int = 0
 
     def to_c(self) -> _LossConfig:
         return _LossConfig(self.clip_eps_low, self.clip_eps_high, self.kl_beta, self.sgt_lambda,
-                           self.loss_agg, self.accumulate_dw, self.dh_dtype, self.chunk_rows)
+                           self.loss_agg, self.accumulate_dw, self.dh_dtype, self.chunk_rows,
+                           self.scored_rows_hint)
 
 
 STATS_FIELDS = ("loss_total", "loss_pg", "loss_kl", "loss_sgt", "mean_ratio", "max_ratio", "mean_k3",
-                "n_scored_tokens", "n_clipped_tokens", "n_zero_grad_tokens", "n_bad_targets")
-STATS_BYTES = 7 * 8 + 4 * 8
+                "n_scored_tokens", "n_clipped_tokens", "n_zero_grad_tokens", "n_bad_targets",
+                "n_unprocessed_rows")
+STATS_BYTES = 7 * 8 + 5 * 8
 
 
 def lib() -> ctypes.CDLL:
@@ -219,7 +222,7 @@ def read_stats(stats: torch.Tensor) -> dict:
     """Copies the device stats block to the host (synchronises) and decodes it."""
     raw = stats.cpu().numpy().tobytes()
     import struct
-    vals = struct.unpack("<7d4q", raw)
+    vals = struct.unpack("<7d5q", raw)
     return dict(zip(STATS_FIELDS, vals))
 
 

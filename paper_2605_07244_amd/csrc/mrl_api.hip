@@ -141,6 +141,7 @@ int check_cfg(const mrl_loss_config* c) {
   if (c->accumulate_dw != 0 && c->accumulate_dw != 1) return MRL_ERR_CONFIG;
   if (c->dh_dtype != MRL_F32 && c->dh_dtype != MRL_BF16) return MRL_ERR_CONFIG;
   if (c->chunk_rows < 0 || c->chunk_rows % kTile != 0 || c->chunk_rows > (1 << 20)) return MRL_ERR_CONFIG;
+  if (c->scored_rows_hint < 0) return MRL_ERR_CONFIG;
   return MRL_OK;
 }
 
@@ -375,7 +376,12 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     Scope sc(MRL_PROF_CONVERT, s);
     launch_transpose(lm_head_w, d, nullptr, at<void>(ws, L.Wt), L.Vp, V, nullptr, 0, 0, d, L.Vp, es, s);
   }
-  for (int64_t c = 0; c < L.n_chunks; ++c) {
+  int64_t n_passes = L.n_chunks;
+  if (cfg->scored_rows_hint > 0) {
+    const int64_t by_hint = (cfg->scored_rows_hint + L.chunk_rows - 1) / L.chunk_rows;
+    n_passes = by_hint < n_passes ? by_hint : n_passes;
+  }
+  for (int64_t c = 0; c < n_passes; ++c) {
     const int64_t c0 = c * L.chunk_rows;
     forward_chunk(hidden, lm_head_w, d, V, bf16, L, ws, c0, bwd, s);
     {
@@ -439,8 +445,9 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
   }
   {
     Scope sc(MRL_PROF_FINAL, s);
-    launch_finalize(at<double>(ws, L.loss_partials), L.epi_blocks_total, n_scored, n_scored + 1, beta,
-                    cfg->sgt_lambda, out_stats, s);
+    launch_finalize(at<double>(ws, L.loss_partials), n_passes * row_epilogue_blocks(L.chunk_rows), n_scored,
+                    n_scored + 1, beta, cfg->sgt_lambda, n_passes * (int64_t)L.chunk_rows, row_index, out_logp,
+                    out_stats, s);
   }
   return last_error();
 }

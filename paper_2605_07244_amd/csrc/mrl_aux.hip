@@ -401,8 +401,13 @@ __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
 
 __global__ __launch_bounds__(256) void k_finalize(const double* parts, int64_t n_blocks,
                                                   const int64_t* n_scored, const int64_t* n_bad,
-                                                  float beta, float lambda, double* out_d, int64_t* out_i) {
+                                                  float beta, float lambda, int64_t rows_enqueued,
+                                                  const int32_t* row_index, float* out_logp,
+                                                  double* out_d, int64_t* out_i) {
   __shared__ double sh[256];
+  // rows the enqueued passes did not cover (only when the caller's hint was too small)
+  for (int64_t i = rows_enqueued + threadIdx.x; i < *n_scored; i += 256)
+    out_logp[row_index[i]] = __builtin_nanf("");
   __shared__ double tot[9];
   for (int k = 0; k < 9; ++k) {
     double acc = 0.0;
@@ -435,6 +440,7 @@ __global__ __launch_bounds__(256) void k_finalize(const double* parts, int64_t n
     out_i[1] = (int64_t)(tot[6] + 0.5);
     out_i[2] = (int64_t)(tot[7] + 0.5);
     out_i[3] = *n_bad;
+    out_i[4] = *n_scored > rows_enqueued ? *n_scored - rows_enqueued : 0;
   }
 }
 
@@ -696,12 +702,12 @@ void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, void* 
 }
 
 void launch_finalize(const double* loss_partials, int64_t n_blocks, const int64_t* n_scored,
-                     const int64_t* n_bad, float beta, float lambda, void* out_stats,
-                     hipStream_t stream) {
+                     const int64_t* n_bad, float beta, float lambda, int64_t rows_enqueued,
+                     const int32_t* row_index, float* out_logp, void* out_stats, hipStream_t stream) {
   double* out_d = static_cast<double*>(out_stats);
   int64_t* out_i = reinterpret_cast<int64_t*>(out_d + 7);
   hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, stream, loss_partials, n_blocks, n_scored, n_bad,
-                     beta, lambda, out_d, out_i);
+                     beta, lambda, rows_enqueued, row_index, out_logp, out_d, out_i);
 }
 
 }  // namespace mrl

@@ -125,9 +125,11 @@ void launch_group_advantages(const float* rewards, const int32_t* group_id, cons
                              float pos_thresh, float* out_adv, float* out_mean, float* out_std,
                              uint8_t* out_flags, hipStream_t stream);
 
+// rows_enqueued: number of compacted rows covered by the enqueued passes; scored rows beyond
+// it (a wrong scored_rows_hint) get NaN log-probs and are counted in the stats.
 void launch_finalize(const double* loss_partials, int64_t n_blocks, const int64_t* n_scored,
-                     const int64_t* n_bad, float beta, float lambda, void* out_stats,
-                     hipStream_t stream);
+                     const int64_t* n_bad, float beta, float lambda, int64_t rows_enqueued,
+                     const int32_t* row_index, float* out_logp, void* out_stats, hipStream_t stream);
 
 // ---- profiling ---------------------------------------------------------------
 void prof_begin(int cls, hipStream_t stream);

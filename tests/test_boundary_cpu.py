@@ -35,8 +35,8 @@ def test_version_and_status_strings():
 
 
 def test_stats_struct_size_matches_header():
-    # 7 doubles + 4 int64 (see mrl_loss_stats)
-    assert binding.STATS_BYTES == 88 and len(binding.STATS_FIELDS) == 11
+    # 7 doubles + 5 int64 (see mrl_loss_stats)
+    assert binding.STATS_BYTES == 96 and len(binding.STATS_FIELDS) == 12
 
 
 P = ctypes.c_void_p
@@ -114,6 +114,7 @@ def test_loss_argument_errors():
     assert _loss(_cfg(accumulate_dw=3)) == -7
     assert _loss(_cfg(dh_dtype=5)) == -7
     assert _loss(_cfg(chunk_rows=300)) == -7
+    assert _loss(_cfg(scored_rows_hint=-5)) == -7
     assert _loss(_cfg(dh_dtype=1), dt=0) == -7               # fp32 path writes fp32 dH only
     assert _loss(good, ws=None) == -6
     assert _loss(good, ws_bytes=1024) == -6
