@@ -4,9 +4,15 @@
 // tile per workgroup (both operands K-contiguous, "NT" form).  Four wave64
 // wavefronts form a 2 x 2 grid, each owning a 128 x 128 sub-tile as 4 x 4
 // MFMA 32x32x16 accumulators (256 accumulator registers per lane).  Operand
-// panels of 64 K-elements are staged through LDS, double-buffered, in rows of
-// 128 bytes whose 16-byte chunks are XOR-swizzled with the row number so that
-// the 128-bit fragment reads of the MFMA operands are bank-conflict free.
+// panels of 32 K-elements go from global memory straight into LDS
+// (global_load ... lds, no staging registers) through a ring of four stages,
+// so loads run three panels ahead of the MFMAs.  LDS rows are 64 bytes whose
+// 16-byte chunks are XOR-swizzled with (row / 4) % 4: a 128-bit LDS read is served
+// 16 lanes (16 rows of one chunk column) per cycle over 64 banks, rows 4 apart
+// share a bank window, and the swizzle spreads them over the four chunk slots, so
+// the fragment reads of the MFMA operands are bank-conflict free; the swizzle is
+// applied on the global side (each lane picks the chunk whose LDS slot it owns)
+// because a direct load writes the wave's 64 x 16 bytes contiguously.
 //
 // The three uses on the scoring path (Sec. 3: log pi(y_t | ...) needs the
 // softmax over the whole vocabulary of the LM-head logits):
@@ -28,9 +34,14 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
-constexpr int TILE_BYTES = BM * BK * 2;            // one operand panel: 32 KB
+constexpr int NSTAGE = 2;                          // LDS double buffer of K panels
+constexpr int TILE_BYTES = BM * BK * 2;            // one operand panel: 32 KB (256 rows x 128 B)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;         // double buffered: 128 KB
+constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;    // 128 KB
+
+// s_waitcnt immediates (gfx9 encoding): wait until at most N vector-memory loads are
+// outstanding, no wait on the export / LDS counters.
+constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
 
@@ -96,29 +107,54 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M || n0 >= N) return;
 
-  // ---- global -> LDS staging: 8 threads cover one 128-byte row, 32 rows per pass
-  const int lc = tid & 7;        // 16-byte chunk within the row
-  const int lr = tid >> 3;       // 0..31
+  // ---- global -> LDS: one direct load moves 8 rows x 128 B (1 KB, contiguous in LDS).
+  // Wave w owns row blocks 8w .. 8w+7 of each operand panel; lane l fills LDS chunk
+  // (row l/8, slot l%8) and therefore fetches logical chunk slot ^ ((row >> 1) & 7).
+  const int lrow = lane >> 3;
   const uint16_t* a_ptr[8];
   const uint16_t* b_ptr[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    int ra = m0 + lr + 32 * i; ra = ra < M ? ra : M - 1;
-    int rb = n0 + lr + 32 * i; rb = rb < N ? rb : N - 1;
+    const int r = (wave * 8 + i) * 8 + lrow;          // row within the 256-row panel
+    const int lchunk = (lane & 7) ^ ((r >> 1) & 7);
+    int ra = m0 + r; ra = ra < M ? ra : M - 1;
+    int rb = n0 + r; rb = rb < N ? rb : N - 1;
     int64_t rowa = ra, rowb = rb;
     if (MODE == MODE_FWD) rowb = p.row_index[rb];
-    a_ptr[i] = p.A + rowa * p.lda + lc * 8;
-    b_ptr[i] = p.B + rowb * p.ldb + lc * 8;
+    a_ptr[i] = p.A + rowa * p.lda + lchunk * 8;
+    b_ptr[i] = p.B + rowb * p.ldb + lchunk * 8;
   }
-  // swizzled LDS write offset of (row lr + 32 i, chunk lc): (row & 7) == (lr & 7)
-  const int st_off = lr * 128 + ((lc ^ (lr & 7)) << 4);
+  // The direct load is issued through inline assembly on purpose: the compiler's wait-count
+  // pass treats a global load that writes LDS as touching both address spaces and then
+  // drains every counter to zero before each LDS read, which serialises the pipeline.
+  // Issued this way the loads are invisible to that pass; their completion is awaited
+  // explicitly below with s_waitcnt vmcnt(0) before the barrier that publishes a panel.
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_base + wave * 8192);
 
-  // ---- fragment read offsets: lane -> row (lane & 31), k-half (lane >> 5)
+  auto load_lds16 = [](const uint16_t* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(g), "s"(lds_addr) : "memory");
+  };
+  // loads i0 .. i0+n-1 (of 8) of both operand panels of K panel kt into ring slot `slot`
+  auto issue_loads = [&](int kt, int slot, int i0, int n) {
+    const uint32_t st = slot * STAGE_BYTES + wave_lds;
+    const int koff = kt * BK;
+#pragma unroll
+    for (int i = i0; i < i0 + n; ++i) {
+      load_lds16(a_ptr[i] + koff, st + i * 1024);
+      load_lds16(b_ptr[i] + koff, st + TILE_BYTES + i * 1024);
+    }
+  };
+
+  // ---- fragment read offsets: lane -> row (lane & 31), k-half (lane >> 5).
+  // A 128-bit LDS read is served 16 lanes per cycle over 64 banks; rows 2 apart share a
+  // bank window (128-byte rows), the swizzle (row / 2) % 8 spreads them over the 8 chunk slots.
   const int frow = lane & 31, fhalf = lane >> 5;
   int a_off[4], b_off[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    const int chunk = ((kk << 1) | fhalf) ^ (frow & 7);
+    const int chunk = ((kk << 1) | fhalf) ^ ((frow >> 1) & 7);
     a_off[kk] = (wm * 128 + frow) * 128 + (chunk << 4);
     b_off[kk] = TILE_BYTES + (wn * 128 + frow) * 128 + (chunk << 4);
   }
@@ -131,61 +167,96 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  u32x4 ra[8], rb[8];
   const int nk = K / BK;
-  if (nk > 0) {
+  bf16x8 af0[4], bf0[4], af1[4], bf1[4];
+  auto read_frags = [&](bf16x8* af, bf16x8* bfr, int kt, int kk) {
+    const int st = (kt & (NSTAGE - 1)) * STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      ra[i] = *reinterpret_cast<const u32x4*>(a_ptr[i]);
-      rb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i]);
+    for (int i = 0; i < 4; ++i) {
+      af[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[kk] + i * 4096);
+      bfr[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[kk] + i * 4096);
     }
+  };
+  auto mma = [&](const bf16x8* af, const bf16x8* bfr) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<u32x4*>(smem + st_off + i * 4096) = ra[i];
-      *reinterpret_cast<u32x4*>(smem + TILE_BYTES + st_off + i * 4096) = rb[i];
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+  };
+  // interleave hint for one "8 LDS reads + 16 MFMAs" group: 1 read, then 2 MFMAs, eight times
+  auto interleave = [] {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
+  };
+
+  // Software pipeline.  Panel kt is loaded during the MFMAs of panel kt-1 (double buffer).
+  // The last 16-wide K step of a panel is multiplied after the barrier that publishes the
+  // next panel, so that the LDS latency of the next panel's first fragments is covered.
+  // The loop body is branch-free (a branch inside it splits the accumulator live ranges
+  // and makes the register allocator spill): the last panel is peeled, and the one load
+  // group that would run past the end re-fetches the last panel into a slot nobody reads.
+  if (nk > 0) {
+    issue_loads(0, 0, 0, 8);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __syncthreads();
+    issue_loads(nk > 1 ? 1 : 0, 1, 0, 8);
+    read_frags(af0, bf0, 0, 0);
+  }
+  for (int kt = 0; kt < nk - 1; ++kt) {
+    // fragments of (kt, 0) are in flight or in registers (af0)
+    read_frags(af1, bf1, kt, 1);
+    mma(af0, bf0);
+    interleave();
+    read_frags(af0, bf0, kt, 2);
+    mma(af1, bf1);
+    interleave();
+    read_frags(af1, bf1, kt, 3);
+    mma(af0, bf0);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    // this thread's part of panel kt+1 has landed, then everyone's; every wave has finished
+    // reading panel kt (its last fragments are in registers), so its slot can be refilled
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __syncthreads();
+    read_frags(af0, bf0, kt + 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // MFMAs of (kt, 3) with the direct loads of panel kt+2 issued in their shadow
+    const int knext = kt + 2 < nk ? kt + 2 : nk - 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#ifndef PROBE_NOGLOAD
+      issue_loads(knext, kt & 1, 2 * i, 2);
+#endif
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = (kt & 1) * STAGE_BYTES;
-    const int nxt = STAGE_BYTES - cur;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      const int koff = (kt + 1) * BK;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        ra[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + koff);
-        rb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + koff);
-      }
-    }
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[4], bfr[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(smem + cur + a_off[kk] + i * 4096);
-        bfr[i] = *reinterpret_cast<const bf16x8*>(smem + cur + b_off[kk] + i * 4096);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        *reinterpret_cast<u32x4*>(smem + nxt + st_off + i * 4096) = ra[i];
-        *reinterpret_cast<u32x4*>(smem + nxt + TILE_BYTES + st_off + i * 4096) = rb[i];
-      }
-    }
-    __syncthreads();
+  if (nk > 0) {
+    const int kt = nk - 1;
+    read_frags(af1, bf1, kt, 1);
+    mma(af0, bf0);
+    interleave();
+    read_frags(af0, bf0, kt, 2);
+    mma(af1, bf1);
+    interleave();
+    read_frags(af1, bf1, kt, 3);
+    mma(af0, bf0);
+    interleave();
+    mma(af1, bf1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
   }
 
   // ---- epilogues.  Accumulator element (i, j, e) of this lane is
   //   row m = m0 + wm*128 + i*32 + 8*(e/4) + 4*(lane>>5) + (e&3)
   //   col n = n0 + wn*128 + j*32 + (lane & 31)
+  __syncthreads();
   const int mrow_base = m0 + wm * 128 + 4 * fhalf;
   const int ncol_base = n0 + wn * 128 + frow;
 
