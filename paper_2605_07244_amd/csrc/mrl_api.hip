@@ -74,7 +74,7 @@ struct Layout {
   size_t counters, row_index, block_counts, zt, part_max, part_sum;
   size_t seq_len, seq_coef, group_count, lse_c, g_c, loss_partials, Z, Pt, Ht, Wt;
   int chunk_rows = 0, n_partials = 0;
-  int64_t n_chunks = 0, Vp = 0, ldz = 0;
+  int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of Z/P and Wt, ldr: of Pt and Ht
   int64_t epi_blocks_total = 0;
 };
 
@@ -91,7 +91,10 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
   L.chunk_rows = chunk_rows;
   L.n_chunks = N > 0 ? (N + chunk_rows - 1) / chunk_rows : 0;
   L.Vp = bf16 ? round_up(V, kTile) : V;
-  L.ldz = L.Vp;
+  // bf16 path: strides are padded by 64 elements (128 B) so that consecutive rows of a tile do
+  // not fall onto the same L2 channel (a power-of-two row stride serialises the panel loads)
+  L.ldz = bf16 ? L.Vp + 64 : L.Vp;
+  L.ldr = bf16 ? chunk_rows + 64 : chunk_rows;
   L.n_partials = bf16 ? fwd_partials_bf16(V) : 1;
   L.epi_blocks_total = L.n_chunks * row_epilogue_blocks(chunk_rows);
   const int64_t nb = (N + 1023) / 1024;
@@ -110,9 +113,9 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
     L.g_c = take(off, (size_t)(N + 1) * 4);
     L.loss_partials = take(off, (size_t)(L.epi_blocks_total + 1) * 10 * 8);
     L.Z = take(off, (size_t)chunk_rows * L.ldz * es);
-    L.Pt = take(off, (size_t)L.Vp * chunk_rows * es);
-    L.Ht = take(off, (size_t)d * chunk_rows * es);
-    L.Wt = take(off, (size_t)d * L.Vp * es);
+    L.Pt = take(off, (size_t)L.Vp * L.ldr * es);
+    L.Ht = take(off, (size_t)d * L.ldr * es);
+    L.Wt = take(off, (size_t)d * L.ldz * es);
   } else if (!bf16) {
     L.Z = take(off, (size_t)chunk_rows * L.ldz * es);
   }
@@ -374,7 +377,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
   }
   if (out_dH) {
     Scope sc(MRL_PROF_CONVERT, s);
-    launch_transpose(lm_head_w, d, nullptr, at<void>(ws, L.Wt), L.Vp, V, nullptr, 0, 0, d, L.Vp, es, s);
+    launch_transpose(lm_head_w, d, nullptr, at<void>(ws, L.Wt), L.ldz, V, nullptr, 0, 0, d, L.Vp, es, s);
   }
   int64_t n_passes = L.n_chunks;
   if (cfg->scored_rows_hint > 0) {
@@ -402,22 +405,22 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     if (!bwd) continue;
     {
       Scope sc(MRL_PROF_CONVERT, s);
-      launch_convert(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Pt), L.chunk_rows, at<float>(ws, L.lse_c),
+      launch_convert(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Pt), L.ldr, at<float>(ws, L.lse_c),
                      at<float>(ws, L.g_c), target_ids, row_index, n_scored, c0, L.chunk_rows, V, (int)L.Vp,
                      bf16, s);
       if (out_dW)
-        launch_transpose(hidden, d, row_index + c0, at<void>(ws, L.Ht), L.chunk_rows, 0, n_scored, c0,
+        launch_transpose(hidden, d, row_index + c0, at<void>(ws, L.Ht), L.ldr, 0, n_scored, c0,
                          L.chunk_rows, d, L.chunk_rows, es, s);
     }
     if (out_dH) {
       Scope sc(MRL_PROF_GEMM_DH, s);
       if (bf16) {
-        launch_gemm_dh_bf16(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Wt), L.Vp, row_index, n_scored, c0,
+        launch_gemm_dh_bf16(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Wt), L.ldz, row_index, n_scored, c0,
                             L.chunk_rows, (int)L.Vp, d, out_dH, cfg->dh_dtype == MRL_F32, s);
       } else {
         GemmF32Args g = {};
         g.A = at<float>(ws, L.Z); g.lda = L.ldz; g.a_rows = nullptr;
-        g.B = at<float>(ws, L.Wt); g.ldb = L.Vp;
+        g.B = at<float>(ws, L.Wt); g.ldb = L.ldz;
         g.C = static_cast<float*>(out_dH); g.ldc = d; g.c_rows = row_index + c0;
         g.M = L.chunk_rows; g.N = d; g.K = V;
         g.n_scored = n_scored; g.chunk_start = c0; g.chunk_rows = L.chunk_rows;
@@ -429,12 +432,12 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
       Scope sc(MRL_PROF_GEMM_DW, s);
       const int overwrite = (c == 0 && !cfg->accumulate_dw) ? 1 : 0;
       if (bf16) {
-        launch_gemm_dw_bf16(at<void>(ws, L.Pt), L.chunk_rows, at<void>(ws, L.Ht), L.chunk_rows, n_scored, c0,
+        launch_gemm_dw_bf16(at<void>(ws, L.Pt), L.ldr, at<void>(ws, L.Ht), L.ldr, n_scored, c0,
                             L.chunk_rows, V, d, out_dW, overwrite, s);
       } else {
         GemmF32Args g = {};
-        g.A = at<float>(ws, L.Pt); g.lda = L.chunk_rows; g.a_rows = nullptr;
-        g.B = at<float>(ws, L.Ht); g.ldb = L.chunk_rows;
+        g.A = at<float>(ws, L.Pt); g.lda = L.ldr; g.a_rows = nullptr;
+        g.B = at<float>(ws, L.Ht); g.ldb = L.ldr;
         g.C = out_dW; g.ldc = d; g.c_rows = nullptr;
         g.M = V; g.N = d; g.K = L.chunk_rows;
         g.n_scored = n_scored; g.chunk_start = c0; g.chunk_rows = L.chunk_rows;

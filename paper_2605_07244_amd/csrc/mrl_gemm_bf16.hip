@@ -37,7 +37,10 @@ constexpr int NTHREADS = 256;
 constexpr int NSTAGE = 2;                          // LDS double buffer of K panels
 constexpr int TILE_BYTES = BM * BK * 2;            // one operand panel: 32 KB (256 rows x 128 B)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
-constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;    // 128 KB
+constexpr int STASH_LD = BM + 8;                   // fp16 elements per row of the epilogue staging tile
+constexpr int STASH_BYTES = BN * STASH_LD * 2;     // 132 KB
+constexpr int PIPE_BYTES = NSTAGE * STAGE_BYTES;   // 128 KB
+constexpr int LDS_BYTES = STASH_BYTES > PIPE_BYTES ? STASH_BYTES : PIPE_BYTES;
 
 // s_waitcnt immediates (gfx9 encoding): wait until at most N vector-memory loads are
 // outstanding, no wait on the export / LDS counters.
@@ -104,6 +107,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
   int tm, tn;
   if (!tile_coords(blockIdx.x, Mt, Nt, tm, tn)) return;
+#ifdef PROBE_SAMETILE
+  tm = 0; tn = 0;
+#endif
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M || n0 >= N) return;
 
@@ -306,8 +312,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         p.part_max[(int64_t)pidx * p.chunk_rows + n] = mx;
         p.part_sum[(int64_t)pidx * p.chunk_rows + n] = s;
       }
-      if (p.zstash != nullptr && n < N) {
-        uint16_t* zrow = p.zstash + (int64_t)n * p.ldz;
+      if (p.zstash != nullptr) {
+        // stage the logits as fp16 in LDS, [token][vocab], for coalesced row stores below
+        unsigned char* srow = smem + (wn * 128 + j * 32 + frow) * (STASH_LD * 2) + (wm * 128 + 4 * fhalf) * 2;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -316,9 +323,21 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
               h[r] = (_Float16)__builtin_amdgcn_fmed3f(acc[i][j][q * 4 + r], -65504.f, 65504.f);
-            const int v = mrow_base + i * 32 + 8 * q;
-            *reinterpret_cast<f16x4*>(zrow + v) = h;
+            *reinterpret_cast<f16x4*>(srow + (i * 32 + 8 * q) * 2) = h;
           }
+      }
+    }
+    if (p.zstash != nullptr) {
+      __syncthreads();
+      // 32 lanes store one 512-byte row segment; a wave instruction covers two token rows
+#pragma unroll 4
+      for (int k = 0; k < 32; ++k) {
+        const int c = tid + NTHREADS * k;
+        const int row = c >> 5, col = c & 31;
+        if (n0 + row < N) {
+          const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * (STASH_LD * 2) + col * 16);
+          *reinterpret_cast<u32x4*>(p.zstash + (int64_t)(n0 + row) * p.ldz + m0 + col * 8) = v;
+        }
       }
     }
   } else if (MODE == MODE_DH) {
@@ -344,9 +363,23 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         }
       }
   } else {
-    // rows = vocabulary ids, cols = hidden index; fp32 accumulate into dW
+    // rows = vocabulary ids, cols = hidden index; fp32 accumulate into dW.  The old values of
+    // one 32-row band are fetched as a batch before any store, so their latencies overlap.
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
+      float old[4][16];
+      if (!p.overwrite) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int v = mrow_base + i * 32 + 8 * (e >> 2) + (e & 3);
+          const float* row = p.dW + (int64_t)(v < p.V ? v : p.V - 1) * p.d;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int n = ncol_base + j * 32;
+            old[j][e] = row[n < p.d ? n : p.d - 1];
+          }
+        }
+      }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int v = mrow_base + i * 32 + 8 * (e >> 2) + (e & 3);
@@ -355,13 +388,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const int n = ncol_base + j * 32;
-            if (n < p.d) {
-              if (p.overwrite) row[n] = acc[i][j][e];
-              else row[n] += acc[i][j][e];
-            }
+            if (n < p.d) row[n] = p.overwrite ? acc[i][j][e] : old[j][e] + acc[i][j][e];
           }
         }
       }
+    }
   }
 }
 
