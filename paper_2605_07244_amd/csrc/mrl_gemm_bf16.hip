@@ -34,6 +34,9 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
+#ifndef LD_SPLIT
+#define LD_SPLIT 6          // load pairs (of 8 per panel) issued right after the barrier; the rest one MFMA group later
+#endif
 constexpr int NSTAGE = 2;                          // LDS double buffer of K panels
 constexpr int TILE_BYTES = BM * BK * 2;            // one operand panel: 32 KB (256 rows x 128 B)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
@@ -47,6 +50,23 @@ constexpr int LDS_BYTES = STASH_BYTES > PIPE_BYTES ? STASH_BYTES : PIPE_BYTES;
 constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
+
+// timing-probe switches (never defined in the library build)
+#ifdef PROBE_NODSREAD
+#define PROBE_RD(x)
+#else
+#define PROBE_RD(x) x
+#endif
+#ifdef PROBE_NOGLOAD
+#define PROBE_LD(x)
+#else
+#define PROBE_LD(x) x
+#endif
+#if defined(PROBE_NOBARRIER) && defined(PROBE_NOGLOAD)
+#define PROBE_BAR(x)
+#else
+#define PROBE_BAR(x) x
+#endif
 
 struct Params {
   const uint16_t* A; int64_t lda; int M;
@@ -209,28 +229,33 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     issue_loads(0, 0, 0, 8);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
-    issue_loads(nk > 1 ? 1 : 0, 1, 0, 8);
+    issue_loads(nk > 1 ? 1 : 0, 1, 0, LD_SPLIT);
     read_frags(af0, bf0, 0, 0);
   }
   for (int kt = 0; kt < nk - 1; ++kt) {
-    // fragments of (kt, 0) are in flight or in registers (af0)
-    read_frags(af1, bf1, kt, 1);
+    // fragments of (kt, 0) are in flight or in registers (af0).  Panel kt+1 goes into the other
+    // slot (released by the barrier that ended iteration kt-1): its first 6 of 8 load pairs were
+    // issued right after that barrier, the rest is issued here, in the shadow of the MFMAs.
+    PROBE_RD(read_frags(af1, bf1, kt, 1));
     mma(af0, bf0);
     interleave();
-    read_frags(af0, bf0, kt, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    PROBE_LD(issue_loads(kt + 1, (kt + 1) & 1, LD_SPLIT, 8 - LD_SPLIT));
+    __builtin_amdgcn_sched_barrier(0);
+    PROBE_RD(read_frags(af0, bf0, kt, 2));
     mma(af1, bf1);
     interleave();
-    read_frags(af1, bf1, kt, 3);
+    PROBE_RD(read_frags(af1, bf1, kt, 3));
     mma(af0, bf0);
     interleave();
     __builtin_amdgcn_sched_barrier(0);
     // this thread's part of panel kt+1 has landed, then everyone's; every wave has finished
     // reading panel kt (its last fragments are in registers), so its slot can be refilled
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-    __syncthreads();
-    read_frags(af0, bf0, kt + 1, 0);
+    PROBE_BAR(__syncthreads());
+    PROBE_RD(read_frags(af0, bf0, kt + 1, 0));
     __builtin_amdgcn_sched_barrier(0);
-    // MFMAs of (kt, 3) with the direct loads of panel kt+2 issued in their shadow
+    // MFMAs of (kt, 3) with the first direct loads of panel kt+2 issued in their shadow
     const int knext = kt + 2 < nk ? kt + 2 : nk - 1;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -238,9 +263,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       for (int j = 0; j < 4; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-#ifndef PROBE_NOGLOAD
-      issue_loads(knext, kt & 1, 2 * i, 2);
-#endif
+      if (i < LD_SPLIT / 2 + (LD_SPLIT & 1)) { PROBE_LD(issue_loads(knext, kt & 1, 2 * i, (2 * i + 2 <= LD_SPLIT) ? 2 : 1)); }
       __builtin_amdgcn_sched_barrier(0);
     }
   }
