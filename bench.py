@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-rows", type=int, default=0)
     ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (debug)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (calibration of the HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1")
@@ -131,6 +133,13 @@ def main():
     elapsed = time.perf_counter() - t0
     prof = mrl.profile_collect()
     mrl.profile_enable(False)
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     stats = mrl.read_stats(out_stats)
     assert stats["n_scored_tokens"] == n_scored and stats["n_unprocessed_rows"] == 0, stats
 
@@ -150,7 +159,8 @@ def main():
     tfile = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tfile):
         try:
-            traffic = json.load(open(tfile)).get(f"{dom}:config{args.config}")
+            rec = json.load(open(tfile)).get(f"{dom}:config{args.config}")
+            traffic = rec["fetch_bytes"] + rec["write_bytes"] if rec else None
         except Exception:
             traffic = None
     roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=MFMA_BF16_PEAK_TFLOPS,
