@@ -153,6 +153,8 @@ def token_logprobs(hidden, lm_head_w, target_ids, token_mask=None, workspace=Non
         raise ValueError("lm_head_w must be [V, d] with the dtype of hidden")
     out_logp = torch.empty(N, dtype=torch.float32, device=hidden.device)
     out_lse = torch.empty(N, dtype=torch.float32, device=hidden.device) if want_lse else None
+    if N == 0:            # empty tensors have no device pointer; the library treats N = 0 as a no-op too
+        return out_logp, out_lse
     if workspace is None:
         workspace = _workspace(token_logprobs_workspace(N, d, V, dt), hidden.device)
     rc = lib().mrl_token_logprobs(_ptr(hidden, name="hidden"), _ptr(lm_head_w, name="lm_head_w"),
