@@ -1,0 +1,147 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The CPU oracle cannot run N x V = 10^11 logits, so it computes, from the inputs alone,
+(i) the log-prob, (ii) dL/dl and (iii) the dH row of SAMPLED scored tokens (one row of
+logits each, fp64), and the whole-batch quantities that need no vocabulary work
+(weights, counts).  Everything else is checked through properties that hold at any size:
+  * <dH, H> = <dW, W>  (both equal sum_n,v dz[n,v] z[n,v]),
+  * sum_v dW[v, :] = 0 (each dz row sums to zero),
+  * unscored slots have zero log-prob and zero dH rows,
+  * loss_total = loss_pg + beta * loss_kl + lambda * loss_sgt, counts match the mask.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mrl_oracle as orc
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+N_SAMPLES = 48
+KINK_MARGIN = 5e-3
+
+
+def _run_full(idx, **over):
+    import paper_2605_07244_amd as mrl
+    from paper_2605_07244_amd import synth
+    sp = synth.spec(idx, **over)
+    b = synth.make(sp, "cuda")
+    B, T, G, N, V, d = (b[k] for k in ("B", "T", "G", "N", "V", "d"))
+    adv, _, _, flags = mrl.group_advantages(b["rewards_all"], b["group_all"], G, b["in_stats"], b["scored"], b["is_own"])
+    adv_o, _, _, flags_o = util.oracle_advantages(b)
+    assert np.array_equal(flags.cpu().numpy(), flags_o)
+    assert np.allclose(adv.cpu().numpy(), adv_o, rtol=2e-6, atol=1e-7)
+    seq_adv = synth.seq_adv_from(adv, b)
+    n_scored = int(b["mask"].sum())
+    lc = mrl.LossConfig(clip_eps_low=sp.clip_eps, clip_eps_high=sp.clip_eps, kl_beta=sp.kl_beta,
+                        sgt_lambda=sp.sgt_lambda, scored_rows_hint=n_scored)       # as bench.py
+    out = mrl.grpo_loss_fwd_bwd(b["H"], b["W"], b["targets"], b["mask"].reshape(-1), b["behav"], b["ref"], seq_adv,
+                                b["seq_group"], b["seq_kind"], B, T, G, lc)
+    torch.cuda.synchronize()
+    st = mrl.read_stats(out["stats"])
+    return mrl, sp, b, seq_adv, out, st, n_scored
+
+
+def _check_sampled(sp, b, seq_adv, out, st, n_scored):
+    B, T, G, N, V, d = (b[k] for k in ("B", "T", "G", "N", "V", "d"))
+    mask_np = b["mask"].cpu().numpy().astype(bool)
+    mflat = mask_np.reshape(-1)
+    cfg = util.cfg_dict(sp)
+    # whole-batch weights from the masks alone
+    c, c_sgt = orc.sequence_weights(mask_np, b["seq_group"].cpu().numpy(), b["seq_kind"].cpu().numpy(), G)
+    c, c_sgt = c.reshape(-1), c_sgt.reshape(-1)
+    rng = np.random.default_rng(1234 + sp.index)
+    scored_idx = np.nonzero(mflat)[0]
+    rows = np.sort(rng.choice(scored_idx, size=N_SAMPLES, replace=False))
+    # always include first / last scored rows (pass boundaries) and an auxiliary row if there is one
+    rows[0], rows[-1] = scored_idx[0], scored_idx[-1]
+    aux = np.nonzero(mflat & np.repeat(b["seq_kind"].cpu().numpy() == 1, T))[0]
+    if aux.size:
+        rows[1] = aux[aux.size // 2]
+    rows = np.unique(rows)
+    ridx = torch.tensor(rows, device="cuda")
+    Hs = util.to_f64(b["H"][ridx])
+    W = util.to_f64(b["W"])
+    ys = b["targets"][ridx].cpu().numpy()
+    logp_o, lse_o = orc.token_logprobs(Hs, W, ys)
+    logp_g = out["logp"][ridx].cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(logp_g - logp_o)) <= util.LOGP_TOL
+    # dL/dl of the sampled rows from the oracle's own log-probs
+    beh = util.to_f64(b["behav"][ridx]); ref = util.to_f64(b["ref"][ridx])
+    A = seq_adv.cpu().numpy().astype(np.float64)[rows // T]
+    kind = b["seq_kind"].cpu().numpy()[rows // T]
+    w, s1, s2, J, dJ, k3, dk3 = orc.token_terms(logp_o, beh, ref, A, cfg["clip_eps_low"], cfg["clip_eps_high"])
+    g = np.where(kind == 0, c[rows] * (-dJ + cfg["kl_beta"] * dk3), -cfg["sgt_lambda"] * c_sgt[rows])
+    dH_o, _, _ = orc.head_backward(Hs, W, ys, g)
+    dH_g = util.to_f64(out["dH"][ridx])
+    # tokens whose ratio sits on a clip edge may legitimately take either branch in fp32
+    near = (kind == 0) & ((np.abs(np.log(w) - np.log1p(-cfg["clip_eps_low"])) < KINK_MARGIN) |
+                          (np.abs(np.log(w) - np.log1p(cfg["clip_eps_high"])) < KINK_MARGIN))
+    assert near.sum() <= max(2, N_SAMPLES // 10)
+    ok = ~near
+    assert util.rel_fro(dH_g[ok], dH_o[ok]) <= util.REL_TOL
+    per_row = np.linalg.norm(dH_g[ok] - dH_o[ok], axis=1) / np.maximum(np.linalg.norm(dH_o[ok], axis=1), 1e-30)
+    assert np.max(per_row[np.linalg.norm(dH_o[ok], axis=1) > 0]) <= 3 * util.REL_TOL
+    return mflat
+
+
+def _check_properties(sp, b, out, st, n_scored, mflat):
+    N, V, d = b["N"], b["V"], b["d"]
+    assert st["n_scored_tokens"] == n_scored and st["n_unprocessed_rows"] == 0 and st["n_bad_targets"] == 0
+    total = st["loss_pg"] + sp.kl_beta * st["loss_kl"] + sp.sgt_lambda * st["loss_sgt"]
+    # beta and lambda are fp32 in the library's configuration block
+    assert abs(st["loss_total"] - total) <= 1e-6 * (abs(st["loss_pg"]) + abs(st["loss_kl"]) + abs(st["loss_sgt"]))
+    assert st["loss_kl"] >= 0 and 0 <= st["n_clipped_tokens"] <= n_scored
+    m = torch.tensor(mflat, device="cuda")
+    assert torch.all(out["logp"][~m] == 0)
+    assert not torch.isnan(out["logp"]).any()
+    # unscored dH rows are zero (checked on a strided subset to bound the time)
+    um = torch.nonzero(~m)[:, 0]
+    if um.numel():
+        assert torch.all(out["dH"][um[:: max(1, um.numel() // 4096)]] == 0)
+    # trace identity and zero column sums, accumulated in fp64 chunk by chunk on the device
+    lhs = 0.0
+    for r0 in range(0, N, 1 << 16):
+        r1 = min(N, r0 + (1 << 16))
+        lhs += float((out["dH"][r0:r1].double() * b["H"][r0:r1].double()).sum())
+    rhs = 0.0
+    colsum = torch.zeros(d, dtype=torch.float64, device="cuda")
+    absum = 0.0
+    for v0 in range(0, V, 1 << 14):
+        v1 = min(V, v0 + (1 << 14))
+        blk = out["dW"][v0:v1].double()
+        rhs += float((blk * b["W"][v0:v1].double()).sum())
+        colsum += blk.sum(dim=0)
+        absum += float(blk.abs().sum())
+    scale = float(out["dW"].double().norm() * b["W"].double().norm())
+    assert abs(lhs - rhs) <= 1e-2 * max(abs(rhs), 1e-3 * scale), (lhs, rhs)
+    assert float(colsum.abs().sum()) <= 1e-2 * absum
+
+
+def test_config2_full_size_sampled():
+    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(2)
+    mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    _check_properties(sp, b, out, st, n_scored, mflat)
+
+
+def test_config3_prp_pool_full_width_sampled():
+    # PRP pooled batch (own + peer rollouts in one group, heavy-tailed peer ratios) at full V and d, 8 of 32 prompts
+    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(3, n_prompts=8)
+    assert st["n_clipped_tokens"] > 0.2 * n_scored          # peer ratios mostly leave the clip band
+    mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    _check_properties(sp, b, out, st, n_scored, mflat)
+
+
+def test_config4_reduced_batch_full_width_sampled():
+    # XGRPO / SGT structure at full V and d with 16 of the 64 prompts (memory-light, same kernels and tiles)
+    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(4, n_prompts=16)
+    assert b["n_aux"] > 0 and st["loss_sgt"] > 0
+    mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    _check_properties(sp, b, out, st, n_scored, mflat)
+
+
+def test_config5_full_size_sampled():
+    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(5)
+    mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    _check_properties(sp, b, out, st, n_scored, mflat)
