@@ -10,7 +10,8 @@
 namespace mrl {
 namespace {
 
-constexpr int kDefaultChunkBf16 = 16384;
+constexpr int kDefaultChunkBf16 = 32768;   // rows per pass: amortises the fp32 dW read-modify-write
+constexpr int kFwdSubChunk = 16384;        // forward launches cover this many rows: their H rows stay in the Infinity Cache
 constexpr int kDefaultChunkF32 = 2048;
 constexpr int64_t kMaxSlots = (int64_t)1 << 30;
 
@@ -179,8 +180,12 @@ void forward_chunk(const void* H, const void* W, int d, int V, bool bf16, const 
   const int64_t* n_scored = at<int64_t>(ws, L.counters);
   Scope sc(MRL_PROF_GEMM_FWD, s);
   if (bf16) {
-    launch_gemm_fwd_bf16(W, H, row_index, n_scored, c0, L.chunk_rows, V, d, at<float>(ws, L.part_max),
-                         at<float>(ws, L.part_sum), stash ? at<void>(ws, L.Z) : nullptr, L.ldz, s);
+    for (int sub = 0; sub < L.chunk_rows; sub += kFwdSubChunk) {
+      const int rows = L.chunk_rows - sub < kFwdSubChunk ? L.chunk_rows - sub : kFwdSubChunk;
+      launch_gemm_fwd_bf16(W, H, row_index, n_scored, c0 + sub, rows, V, d, at<float>(ws, L.part_max) + sub,
+                           at<float>(ws, L.part_sum) + sub, L.chunk_rows,
+                           stash ? at<uint16_t>(ws, L.Z) + (size_t)sub * L.ldz : nullptr, L.ldz, s);
+    }
   } else {
     GemmF32Args g = {};
     g.A = static_cast<const float*>(H); g.lda = d; g.a_rows = row_index + c0;

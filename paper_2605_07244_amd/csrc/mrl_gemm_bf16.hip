@@ -75,7 +75,7 @@ struct Params {
   const int32_t* row_index;   // already offset to the chunk start
   const int64_t* n_scored; int64_t chunk_start; int chunk_rows;
   // FWD
-  float* part_max; float* part_sum; uint16_t* zstash; int64_t ldz; int V;
+  float* part_max; float* part_sum; int64_t part_stride; uint16_t* zstash; int64_t ldz; int V;
   // DH
   void* dH; int dh_f32; int d;
   // DW
@@ -332,8 +332,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       }
       s += __shfl_xor(s, 32);
       if (fhalf == 0 && n < N) {
-        p.part_max[(int64_t)pidx * p.chunk_rows + n] = mx;
-        p.part_sum[(int64_t)pidx * p.chunk_rows + n] = s;
+        p.part_max[(int64_t)pidx * p.part_stride + n] = mx;
+        p.part_sum[(int64_t)pidx * p.part_stride + n] = s;
       }
       if (p.zstash != nullptr) {
         // stage the logits as fp16 in LDS, [token][vocab], for coalesced row stores below
@@ -436,7 +436,7 @@ void launch(const Params& p, hipStream_t stream) {
 
 void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                          int V, int d, float* part_max, float* part_sum,
+                          int V, int d, float* part_max, float* part_sum, int64_t part_stride,
                           void* zstash, int64_t ldz, hipStream_t stream) {
   Params p = {};
   p.A = static_cast<const uint16_t*>(W); p.lda = d; p.M = V;
@@ -444,7 +444,7 @@ void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index
   p.K = d;
   p.row_index = row_index + chunk_start;
   p.n_scored = n_scored; p.chunk_start = chunk_start; p.chunk_rows = chunk_rows;
-  p.part_max = part_max; p.part_sum = part_sum;
+  p.part_max = part_max; p.part_sum = part_sum; p.part_stride = part_stride;
   p.zstash = static_cast<uint16_t*>(zstash); p.ldz = ldz; p.V = V; p.d = d;
   launch<MODE_FWD>(p, stream);
 }

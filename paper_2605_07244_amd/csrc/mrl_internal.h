@@ -21,11 +21,11 @@ inline int fwd_partials_bf16(int V) { return 2 * (int)((V + kTile - 1) / kTile);
 // select the rows this launch covers (valid rows = clamp(n_scored - chunk_start, 0, chunk_rows)).
 
 // Forward: A = W [V, d], B = H rows gathered through row_index[chunk_start + n].
-// Writes per-row partials part_max/part_sum[(2*tile_m + wave_m) * chunk_rows + n]
-// and, when zstash != nullptr, the logits as fp16 into zstash[n * ldz + v].
+// Writes per-row partials part_max/part_sum[(2*tile_m + wave_m) * part_stride + n]
+// and, when zstash != nullptr, the logits as fp16 into zstash[n * ldz + v] (n = row within this launch).
 void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                          int V, int d, float* part_max, float* part_sum,
+                          int V, int d, float* part_max, float* part_sum, int64_t part_stride,
                           void* zstash, int64_t ldz, hipStream_t stream);
 
 // dH: A = P [chunk_rows, Vp] (bf16 dz), B = Wt [d, Vp]; row m goes to
