@@ -34,8 +34,11 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
-#ifndef LD_SPLIT
-#define LD_SPLIT 6          // load pairs (of 8 per panel) issued right after the barrier; the rest one MFMA group later
+#ifndef LD_GROUPS
+#define LD_GROUPS 8         // MFMA groups (of 16 per K panel) over which a panel's 16 direct loads are spread
+#endif
+#ifndef PF_DIST
+#define PF_DIST 3           // L2 prefetch distance in K panels (0 = off)
 #endif
 constexpr int NSTAGE = 2;                          // LDS double buffer of K panels
 constexpr int TILE_BYTES = BM * BK * 2;            // one operand panel: 32 KB (256 rows x 128 B)
@@ -83,29 +86,41 @@ struct Params {
 };
 
 // Workgroup -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs,
-// each with its own L2; 32 consecutive workgroups of one XCD form a 4 x 8
+// each with its own L2; 32 consecutive workgroups of one XCD form an 8 x 4
 // super-tile so that they share operand panels in that L2, and super-tiles are
 // numbered N-fastest so that the XCDs walk the same A rows at the same time.
-constexpr int SUP_M = 4, SUP_N = 8, NXCD = 8;
+#ifndef SUPM
+#define SUPM 8
+#define SUPN 4
+#endif
+constexpr int SUP_M = SUPM, SUP_N = SUPN, NXCD = 8;
 __host__ __device__ inline int num_blocks(int Mt, int Nt) {
   int s = ((Mt + SUP_M - 1) / SUP_M) * ((Nt + SUP_N - 1) / SUP_N);
   return (s + NXCD - 1) / NXCD * NXCD * (SUP_M * SUP_N);
 }
-__device__ inline bool tile_coords(int bid, int Mt, int Nt, int& tm, int& tn) {
+__device__ inline bool tile_coords(int bid, int Mt, int Nt, int& tm, int& tn, int& sm, int& sn) {
   const int sNt = (Nt + SUP_N - 1) / SUP_N, sMt = (Mt + SUP_M - 1) / SUP_M;
   const int xcd = bid % NXCD, local = bid / NXCD;
   const int q = local / (SUP_M * SUP_N), within = local % (SUP_M * SUP_N);
   const int s = q * NXCD + xcd;
   if (s >= sMt * sNt) return false;
-  tm = (s / sNt) * SUP_M + within % SUP_M;
-  tn = (s % sNt) * SUP_N + within / SUP_M;
+  sm = within % SUP_M; sn = within / SUP_M;
+  tm = (s / sNt) * SUP_M + sm;
+  tn = (s % sNt) * SUP_N + sn;
   return tm < Mt && tn < Nt;
 }
 
 __device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
+#ifdef PROBE_CLOCK
+__device__ unsigned long long g_probe_clk[4];
+#endif
+
 template <int MODE>
 __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
+#ifdef PROBE_CLOCK
+  const unsigned long long c0 = clock64(), w0 = wall_clock64();
+#endif
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -125,8 +140,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   if (MODE == MODE_DW && nvalid == 0 && !p.overwrite) return;
 
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
-  int tm, tn;
-  if (!tile_coords(blockIdx.x, Mt, Nt, tm, tn)) return;
+  int tm, tn, sm, sn;
+  if (!tile_coords(blockIdx.x, Mt, Nt, tm, tn, sm, sn)) return;
 #ifdef PROBE_SAMETILE
   tm = 0; tn = 0;
 #endif
@@ -171,6 +186,32 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       load_lds16(a_ptr[i] + koff, st + i * 1024);
       load_lds16(b_ptr[i] + koff, st + TILE_BYTES + i * 1024);
     }
+  };
+
+  // ---- L2 prefetch.  The 32 workgroups of a super-tile run on one XCD and read the same 8 A
+  // and 4 B panels per K step; whoever asks first for a 128-byte line waits for the fabric
+  // (memory-side cache or HBM), far longer than the double buffer covers.  So each workgroup
+  // touches a share of the super-tile's lines PF_DIST panels ahead: one direct load of 4 bytes
+  // per lane into an LDS pad nobody reads, one 128-byte line (a row's whole K panel) per lane.
+  // Waves 0 / 2 cover a quarter of the A rows each (two workgroups per line), waves 1 / 3 an
+  // eighth of the B rows in each half wave.
+  const uint16_t* pf_ptr;
+  {
+    int r;
+    if ((wave & 1) == 0) {
+      r = m0 + ((sn + wave) & 3) * 64 + lane; r = r < M ? r : M - 1;
+      pf_ptr = p.A + (int64_t)r * p.lda;
+    } else {
+      r = n0 + ((sm + (wave - 1) + 4 * (lane >> 5)) & 7) * 32 + (lane & 31); r = r < N ? r : N - 1;
+      int64_t rowb = r;
+      if (MODE == MODE_FWD) rowb = p.row_index[r];
+      pf_ptr = p.B + rowb * p.ldb;
+    }
+  }
+  const uint32_t pf_lds = __builtin_amdgcn_readfirstlane(lds_base + PIPE_BYTES + wave * 256);
+  auto prefetch = [&](int kt) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(pf_ptr + kt * BK), "s"(pf_lds) : "memory");
   };
 
   // ---- fragment read offsets: lane -> row (lane & 31), k-half (lane >> 5).
@@ -219,53 +260,69 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     }
   };
 
-  // Software pipeline.  Panel kt is loaded during the MFMAs of panel kt-1 (double buffer).
+  // Software pipeline.  Panel kt+1 is loaded during the MFMAs of panel kt (double buffer).
   // The last 16-wide K step of a panel is multiplied after the barrier that publishes the
-  // next panel, so that the LDS latency of the next panel's first fragments is covered.
+  // next panel, so that the LDS latency of the next panel's first fragments is covered and
+  // the freed slot starts refilling one K step early.  An iteration is 16 groups of 4 MFMAs
+  // (one A fragment against the four B fragments); counted from that barrier, the 16 direct
+  // loads of a panel are spread over the first LD_GROUPS groups, each issued in the shadow of
+  // a group's MFMAs, and the fragments of the next K step are read two per group.
   // The loop body is branch-free (a branch inside it splits the accumulator live ranges
-  // and makes the register allocator spill): the last panel is peeled, and the one load
-  // group that would run past the end re-fetches the last panel into a slot nobody reads.
+  // and makes the register allocator spill): the last panel is peeled, and the loads that
+  // would run past the end re-fetch the last panel into a slot nobody reads.
+  auto issue_group = [&](int kt, int slot, int g) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if (j * LD_GROUPS / 16 == g) {
+        const uint32_t st = slot * STAGE_BYTES + wave_lds + (j >> 1) * 1024;
+        if (j & 1) load_lds16(b_ptr[j >> 1] + kt * BK, st + TILE_BYTES);
+        else load_lds16(a_ptr[j >> 1] + kt * BK, st);
+      }
+  };
+  // one K step: multiply fragments (ca, cb); meanwhile read K step kk_next of the panel at
+  // LDS offset st into (na, nb) (skipped if kk_next < 0) and issue load groups g0 .. g0+3
+  auto kstep = [&](const bf16x8* ca, const bf16x8* cb, bf16x8* na, bf16x8* nb, int st, int kk_next,
+                   int kt_load, int slot_load, int g0, int kt_pre) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (kk_next >= 0) {
+        PROBE_RD(na[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[kk_next & 3] + i * 4096));
+        PROBE_RD(nb[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[kk_next & 3] + i * 4096));
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      PROBE_LD(issue_group(kt_load, slot_load, g0 + i));
+      if (PF_DIST > 0 && g0 + i == LD_GROUPS - 1) { PROBE_LD(prefetch(kt_pre)); }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
   if (nk > 0) {
     issue_loads(0, 0, 0, 8);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
-    issue_loads(nk > 1 ? 1 : 0, 1, 0, LD_SPLIT);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);
+#ifdef PROBE_NOGLOAD
+    for (int g = 4; g < 16; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);   // both slots hold real data
+#endif
     read_frags(af0, bf0, 0, 0);
   }
   for (int kt = 0; kt < nk - 1; ++kt) {
-    // fragments of (kt, 0) are in flight or in registers (af0).  Panel kt+1 goes into the other
-    // slot (released by the barrier that ended iteration kt-1): its first 6 of 8 load pairs were
-    // issued right after that barrier, the rest is issued here, in the shadow of the MFMAs.
-    PROBE_RD(read_frags(af1, bf1, kt, 1));
-    mma(af0, bf0);
-    interleave();
-    __builtin_amdgcn_sched_barrier(0);
-    PROBE_LD(issue_loads(kt + 1, (kt + 1) & 1, LD_SPLIT, 8 - LD_SPLIT));
-    __builtin_amdgcn_sched_barrier(0);
-    PROBE_RD(read_frags(af0, bf0, kt, 2));
-    mma(af1, bf1);
-    interleave();
-    PROBE_RD(read_frags(af1, bf1, kt, 3));
-    mma(af0, bf0);
-    interleave();
-    __builtin_amdgcn_sched_barrier(0);
-    // this thread's part of panel kt+1 has landed, then everyone's; every wave has finished
+    const int st0 = (kt & 1) * STAGE_BYTES;
+    const int kpre = kt + PF_DIST < nk ? kt + PF_DIST : nk - 1;
+    kstep(af0, bf0, af1, bf1, st0, 1, kt + 1, (kt + 1) & 1, 4, kpre);
+    kstep(af1, bf1, af0, bf0, st0, 2, kt + 1, (kt + 1) & 1, 8, kpre);
+    kstep(af0, bf0, af1, bf1, st0, 3, kt + 1, (kt + 1) & 1, 12, kpre);
+    // this thread's part of panel kt+1 has landed (loads complete in order: only the prefetch
+    // issued after them may still be in flight), then everyone's; every wave has finished
     // reading panel kt (its last fragments are in registers), so its slot can be refilled
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(PF_DIST > 0 ? 1 : 0));
     PROBE_BAR(__syncthreads());
     PROBE_RD(read_frags(af0, bf0, kt + 1, 0));
     __builtin_amdgcn_sched_barrier(0);
-    // MFMAs of (kt, 3) with the first direct loads of panel kt+2 issued in their shadow
-    const int knext = kt + 2 < nk ? kt + 2 : nk - 1;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af1[i], bf1[j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (i < LD_SPLIT / 2 + (LD_SPLIT & 1)) { PROBE_LD(issue_loads(knext, kt & 1, 2 * i, (2 * i + 2 <= LD_SPLIT) ? 2 : 1)); }
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    kstep(af1, bf1, nullptr, nullptr, 0, -1, kt + 2 < nk ? kt + 2 : nk - 1, kt & 1, 0, kpre);
   }
   if (nk > 0) {
     const int kt = nk - 1;
@@ -282,6 +339,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
   }
 
+#ifdef PROBE_CLOCK
+  if (blockIdx.x == 8 && threadIdx.x == 0) { g_probe_clk[0] = clock64() - c0; g_probe_clk[1] = wall_clock64() - w0; }
+#endif
   // ---- epilogues.  Accumulator element (i, j, e) of this lane is
   //   row m = m0 + wm*128 + i*32 + 8*(e/4) + 4*(lane>>5) + (e&3)
   //   col n = n0 + wn*128 + j*32 + (lane & 31)
