@@ -2,24 +2,26 @@
 //
 // One kernel body computes C[m][n] = sum_k A[m][k] * B[n][k] for a 256 x 256
 // tile per workgroup (both operands K-contiguous, "NT" form).  Four wave64
-// wavefronts form a 2 x 2 grid, each owning a 128 x 128 sub-tile as 4 x 4
-// MFMA 32x32x16 accumulators (256 accumulator registers per lane).  Operand
-// panels of 32 K-elements go from global memory straight into LDS
-// (global_load ... lds, no staging registers) through a ring of four stages,
-// so loads run three panels ahead of the MFMAs.  LDS rows are 64 bytes whose
-// 16-byte chunks are XOR-swizzled with (row / 4) % 4: a 128-bit LDS read is served
-// 16 lanes (16 rows of one chunk column) per cycle over 64 banks, rows 4 apart
-// share a bank window, and the swizzle spreads them over the four chunk slots, so
-// the fragment reads of the MFMA operands are bank-conflict free; the swizzle is
+// wavefronts form a 2 x 2 grid, each owning a 128 x 128 sub-tile as 8 x 8
+// MFMA 16x16x32 accumulators (256 accumulator registers per lane).  The
+// 16x16x32 shape is chosen over 32x32x16 for energy: with real (random-mantissa)
+// operands the chip is power-limited, and an MFMA-only loop sustains about 13 %
+// more FLOP/s with the 16 x 16 shape.  Operand panels of 64 K-elements go from
+// global memory straight into LDS (global_load ... lds, no staging registers)
+// into a double buffer.  LDS rows are 128 bytes whose 16-byte chunks are
+// XOR-swizzled with (row / 2) % 8: a 128-bit LDS read is served 16 lanes (16
+// rows of one chunk column) per cycle over 64 banks, rows 2 apart share a bank
+// window, and the swizzle spreads them over the eight chunk slots, so the
+// fragment reads of the MFMA operands are bank-conflict free; the swizzle is
 // applied on the global side (each lane picks the chunk whose LDS slot it owns)
 // because a direct load writes the wave's 64 x 16 bytes contiguously.
 //
 // The three uses on the scoring path (Sec. 3: log pi(y_t | ...) needs the
 // softmax over the whole vocabulary of the LM-head logits):
 //   FWD: A = W (vocabulary rows), B = H (token rows, gathered).  The MFMA result
-//        layout keeps 16 rows x 1 column per lane, so putting the vocabulary on
+//        layout keeps 4 rows x 1 column per lane, so putting the vocabulary on
 //        the M side makes the max / sum-exp reduction over the vocabulary an
-//        in-register reduction with a single cross-lane step.
+//        in-register reduction with two cross-lane steps.
 //   DH : A = dz rows (tokens), B = W^T;  rows are scattered to the padded slots.
 //   DW : A = dz^T (vocabulary rows), B = H^T; fp32 read-modify-write of dW.
 #include "mrl_internal.h"
@@ -28,7 +30,7 @@ namespace mrl {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
@@ -64,6 +66,11 @@ enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
 #define PROBE_LD(x)
 #else
 #define PROBE_LD(x) x
+#endif
+#if PF_DIST > 0 && !defined(PROBE_NOGLOAD)
+#define PF_PENDING 1        // direct loads allowed in flight at the barrier: the panel's prefetch
+#else
+#define PF_PENDING 0
 #endif
 #if defined(PROBE_NOBARRIER) && defined(PROBE_NOGLOAD)
 #define PROBE_BAR(x)
@@ -111,6 +118,21 @@ __device__ inline bool tile_coords(int bid, int Mt, int Nt, int& tm, int& tn, in
 }
 
 __device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// The MFMA is issued through inline assembly with the accumulator tied in place in an
+// accumulation register: left to the register allocator, a few of the 64 accumulator tuples
+// (which fill the accumulation file completely) end up rotating through copies every iteration.
+// Consecutive MFMAs here never touch the same accumulator, so no wait states are needed
+// between them; the reads after the K loop are fenced by drain_mfma() below.
+__device__ __forceinline__ void mfma16(f32x4& c, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+// Wait states between the last MFMAs of the K loop and the first ordinary read of their
+// results (the hazard checker of the compiler does not look into inline assembly).
+__device__ __forceinline__ void drain_mfma(f32x4 (&r)[8]) {
+  asm volatile("s_nop 15\n\ts_nop 15"
+               : "+a"(r[0]), "+a"(r[1]), "+a"(r[2]), "+a"(r[3]), "+a"(r[4]), "+a"(r[5]), "+a"(r[6]), "+a"(r[7]));
+}
 
 #ifdef PROBE_CLOCK
 __device__ unsigned long long g_probe_clk[4];
@@ -214,59 +236,38 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
                  :: "v"(pf_ptr + kt * BK), "s"(pf_lds) : "memory");
   };
 
-  // ---- fragment read offsets: lane -> row (lane & 31), k-half (lane >> 5).
-  // A 128-bit LDS read is served 16 lanes per cycle over 64 banks; rows 2 apart share a
-  // bank window (128-byte rows), the swizzle (row / 2) % 8 spreads them over the 8 chunk slots.
-  const int frow = lane & 31, fhalf = lane >> 5;
-  int a_off[4], b_off[4];
+  // ---- fragment read offsets.  A 16x16x32 operand fragment: lane -> row (lane & 15),
+  // 16-byte K chunk (lane >> 4) of a 32-wide K step.  A 128-bit LDS read is served 16 lanes
+  // per cycle over 64 banks; rows 2 apart share a bank window (128-byte rows), the swizzle
+  // (row / 2) % 8 spreads the 16 rows of a fragment over distinct banks.
+  const int frow = lane & 15, fq = lane >> 4;
+  int a_off[2], b_off[2];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const int chunk = ((kk << 1) | fhalf) ^ ((frow >> 1) & 7);
-    a_off[kk] = (wm * 128 + frow) * 128 + (chunk << 4);
-    b_off[kk] = TILE_BYTES + (wn * 128 + frow) * 128 + (chunk << 4);
+  for (int ks = 0; ks < 2; ++ks) {
+    const int chunk = ((ks << 2) | fq) ^ ((frow >> 1) & 7);
+    a_off[ks] = (wm * 128 + frow) * 128 + (chunk << 4);
+    b_off[ks] = TILE_BYTES + (wn * 128 + frow) * 128 + (chunk << 4);
   }
 
-  f32x16 acc[4][4];
+  f32x4 acc[8][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
-  bf16x8 af0[4], bf0[4], af1[4], bf1[4];
-  auto read_frags = [&](bf16x8* af, bf16x8* bfr, int kt, int kk) {
-    const int st = (kt & (NSTAGE - 1)) * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      af[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[kk] + i * 4096);
-      bfr[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[kk] + i * 4096);
-    }
-  };
-  auto mma = [&](const bf16x8* af, const bf16x8* bfr) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-  };
-  // interleave hint for one "8 LDS reads + 16 MFMAs" group: 1 read, then 2 MFMAs, eight times
-  auto interleave = [] {
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-    }
-  };
+  bf16x8 fa0[8], fb0[8], fa1[8], fb1[8];   // fragments of the two K steps of a panel
 
   // Software pipeline.  Panel kt+1 is loaded during the MFMAs of panel kt (double buffer).
-  // The last 16-wide K step of a panel is multiplied after the barrier that publishes the
-  // next panel, so that the LDS latency of the next panel's first fragments is covered and
-  // the freed slot starts refilling one K step early.  An iteration is 16 groups of 4 MFMAs
-  // (one A fragment against the four B fragments); counted from that barrier, the 16 direct
-  // loads of a panel are spread over the first LD_GROUPS groups, each issued in the shadow of
-  // a group's MFMAs, and the fragments of the next K step are read two per group.
+  // A panel is two 32-wide K steps of 8 groups; a group multiplies one A fragment with the
+  // eight B fragments (8 MFMAs, the A operand stays put) and meanwhile reads one A and one B
+  // fragment of the next K step.  The barrier that publishes panel kt+1 (and frees the slot
+  // of panel kt, whose last fragments are in registers by then) sits between the two K steps,
+  // so the LDS latency of the next panel's first fragments is covered by the second K step.
+  // Counted from that barrier, the 16 direct loads of the panel after next are spread over
+  // the first LD_GROUPS groups, each issued in the shadow of a group's MFMAs.
   // The loop body is branch-free (a branch inside it splits the accumulator live ranges
   // and makes the register allocator spill): the last panel is peeled, and the loads that
   // would run past the end re-fetch the last panel into a slot nobody reads.
@@ -279,23 +280,32 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         else load_lds16(a_ptr[j >> 1] + kt * BK, st);
       }
   };
-  // one K step: multiply fragments (ca, cb); meanwhile read K step kk_next of the panel at
-  // LDS offset st into (na, nb) (skipped if kk_next < 0) and issue load groups g0 .. g0+3
-  auto kstep = [&](const bf16x8* ca, const bf16x8* cb, bf16x8* na, bf16x8* nb, int st, int kk_next,
+  // one K step: multiply fragments (ca, cb); meanwhile read K step ks_next of the panel at LDS
+  // offset st into (na, nb) (skipped if ks_next < 0) and issue load groups g0 .. g0+7
+  auto kstep = [&](const bf16x8* ca, const bf16x8* cb, bf16x8* na, bf16x8* nb, int st, int ks_next,
                    int kt_load, int slot_load, int g0, int kt_pre) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (kk_next >= 0) {
-        PROBE_RD(na[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[kk_next & 3] + i * 4096));
-        PROBE_RD(nb[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[kk_next & 3] + i * 4096));
+    for (int i = 0; i < 8; ++i) {
+      if (ks_next >= 0) {
+        PROBE_RD(na[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[ks_next & 1] + i * 2048));
+        PROBE_RD(nb[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks_next & 1] + i * 2048));
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 8; ++j)
+        mfma16(acc[i][j], ca[i], cb[j]);
       __builtin_amdgcn_sched_barrier(0);
-      PROBE_LD(issue_group(kt_load, slot_load, g0 + i));
-      if (PF_DIST > 0 && g0 + i == LD_GROUPS - 1) { PROBE_LD(prefetch(kt_pre)); }
+      if (g0 >= 0) {
+        PROBE_LD(issue_group(kt_load, slot_load, g0 + i));
+        if (PF_DIST > 0 && g0 + i == LD_GROUPS - 1) { PROBE_LD(prefetch(kt_pre)); }
+      }
       __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto read_frags = [&](bf16x8* af, bf16x8* bfr, int st, int ks) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      af[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[ks] + i * 2048);
+      bfr[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks] + i * 2048);
     }
   };
   if (nk > 0) {
@@ -303,50 +313,41 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
 #pragma unroll
-    for (int g = 0; g < 4; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);
+    for (int g = 0; g < 8; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);
 #ifdef PROBE_NOGLOAD
-    for (int g = 4; g < 16; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);   // both slots hold real data
+    for (int g = 8; g < 16; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);   // both slots hold real data
 #endif
-    read_frags(af0, bf0, 0, 0);
+    // keeps the invariant of the loop: one prefetch follows the last load of every panel
+    if (PF_PENDING && LD_GROUPS <= 8) prefetch(PF_DIST < nk ? PF_DIST : nk - 1);
+    read_frags(fa0, fb0, 0, 0);
   }
   for (int kt = 0; kt < nk - 1; ++kt) {
-    const int st0 = (kt & 1) * STAGE_BYTES;
+    const int st0 = (kt & 1) * STAGE_BYTES, st1 = STAGE_BYTES - st0;
     const int kpre = kt + PF_DIST < nk ? kt + PF_DIST : nk - 1;
-    kstep(af0, bf0, af1, bf1, st0, 1, kt + 1, (kt + 1) & 1, 4, kpre);
-    kstep(af1, bf1, af0, bf0, st0, 2, kt + 1, (kt + 1) & 1, 8, kpre);
-    kstep(af0, bf0, af1, bf1, st0, 3, kt + 1, (kt + 1) & 1, 12, kpre);
+    kstep(fa0, fb0, fa1, fb1, st0, 1, kt + 1, (kt + 1) & 1, 8, kpre);
     // this thread's part of panel kt+1 has landed (loads complete in order: only the prefetch
     // issued after them may still be in flight), then everyone's; every wave has finished
     // reading panel kt (its last fragments are in registers), so its slot can be refilled
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(PF_DIST > 0 ? 1 : 0));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(PF_PENDING));
     PROBE_BAR(__syncthreads());
-    PROBE_RD(read_frags(af0, bf0, kt + 1, 0));
-    __builtin_amdgcn_sched_barrier(0);
-    kstep(af1, bf1, nullptr, nullptr, 0, -1, kt + 2 < nk ? kt + 2 : nk - 1, kt & 1, 0, kpre);
+    kstep(fa1, fb1, fa0, fb0, st1, 0, kt + 2 < nk ? kt + 2 : nk - 1, kt & 1, 0, kpre);
   }
   if (nk > 0) {
-    const int kt = nk - 1;
-    read_frags(af1, bf1, kt, 1);
-    mma(af0, bf0);
-    interleave();
-    read_frags(af0, bf0, kt, 2);
-    mma(af1, bf1);
-    interleave();
-    read_frags(af1, bf1, kt, 3);
-    mma(af0, bf0);
-    interleave();
-    mma(af1, bf1);
+    const int st0 = ((nk - 1) & 1) * STAGE_BYTES;
+    kstep(fa0, fb0, fa1, fb1, st0, 1, 0, 0, -1, 0);
+    kstep(fa1, fb1, nullptr, nullptr, 0, -1, 0, 0, -1, 0);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
+    drain_mfma(acc[7]);
   }
 
 #ifdef PROBE_CLOCK
   if (blockIdx.x == 8 && threadIdx.x == 0) { g_probe_clk[0] = clock64() - c0; g_probe_clk[1] = wall_clock64() - w0; }
 #endif
   // ---- epilogues.  Accumulator element (i, j, e) of this lane is
-  //   row m = m0 + wm*128 + i*32 + 8*(e/4) + 4*(lane>>5) + (e&3)
-  //   col n = n0 + wn*128 + j*32 + (lane & 31)
+  //   row m = m0 + wm*128 + i*16 + 4*(lane>>4) + e
+  //   col n = n0 + wn*128 + j*16 + (lane & 15)
   __syncthreads();
-  const int mrow_base = m0 + wm * 128 + 4 * fhalf;
+  const int mrow_base = m0 + wm * 128 + 4 * fq;
   const int ncol_base = n0 + wn * 128 + frow;
 
   if (MODE == MODE_FWD) {
@@ -355,59 +356,55 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     const bool full = (m0 + BM <= p.V);
     const int pidx = tm * 2 + wm;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = ncol_base + j * 32;
+    for (int j = 0; j < 8; ++j) {
+      const int n = ncol_base + j * 16;
       float mx = -INFINITY;
       if (full) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, acc[i][j][e]);
+          for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[i][j][e]);
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int v = mrow_base + i * 32 + 8 * (e >> 2) + (e & 3);
-            mx = v < p.V ? fmaxf(mx, acc[i][j][e]) : mx;
-          }
+          for (int e = 0; e < 4; ++e) mx = (mrow_base + i * 16 + e) < p.V ? fmaxf(mx, acc[i][j][e]) : mx;
       }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float mneg = (mx == -INFINITY) ? 0.f : -mx * LOG2E;
       float s = 0.f;
       if (full) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) s += exp2_fast(fmaf(acc[i][j][e], LOG2E, mneg));
+          for (int e = 0; e < 4; ++e) s += exp2_fast(fmaf(acc[i][j][e], LOG2E, mneg));
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int v = mrow_base + i * 32 + 8 * (e >> 2) + (e & 3);
+          for (int e = 0; e < 4; ++e) {
             const float t = exp2_fast(fmaf(acc[i][j][e], LOG2E, mneg));
-            s += v < p.V ? t : 0.f;
+            s += (mrow_base + i * 16 + e) < p.V ? t : 0.f;
           }
       }
+      s += __shfl_xor(s, 16);
       s += __shfl_xor(s, 32);
-      if (fhalf == 0 && n < N) {
+      if (fq == 0 && n < N) {
         p.part_max[(int64_t)pidx * p.part_stride + n] = mx;
         p.part_sum[(int64_t)pidx * p.part_stride + n] = s;
       }
       if (p.zstash != nullptr) {
         // stage the logits as fp16 in LDS, [token][vocab], for coalesced row stores below
-        unsigned char* srow = smem + (wn * 128 + j * 32 + frow) * (STASH_LD * 2) + (wm * 128 + 4 * fhalf) * 2;
+        unsigned char* srow = smem + (wn * 128 + j * 16 + frow) * (STASH_LD * 2) + (wm * 128 + 4 * fq) * 2;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i) {
+          f16x4 h;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            f16x4 h;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-              h[r] = (_Float16)__builtin_amdgcn_fmed3f(acc[i][j][q * 4 + r], -65504.f, 65504.f);
-            *reinterpret_cast<f16x4*>(srow + (i * 32 + 8 * q) * 2) = h;
-          }
+          for (int e = 0; e < 4; ++e)
+            h[e] = (_Float16)__builtin_amdgcn_fmed3f(acc[i][j][e], -65504.f, 65504.f);
+          *reinterpret_cast<f16x4*>(srow + i * 32) = h;
+        }
       }
     }
     if (p.zstash != nullptr) {
@@ -425,52 +422,68 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     }
   } else if (MODE == MODE_DH) {
     // rows = token rows of the chunk (scattered to their slots), cols = hidden index
+    if (p.dh_f32) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = mrow_base + i * 32 + 8 * (e >> 2) + (e & 3);
-        if (m < M) {
-          const int64_t slot = p.row_index[m];
+        for (int e = 0; e < 4; ++e) {
+          const int m = mrow_base + i * 16 + e;
+          if (m < M) {
+            float* row = reinterpret_cast<float*>(p.dH) + (int64_t)p.row_index[m] * p.d;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int n = ncol_base + j * 32;
-            if (n < p.d) {
-              if (p.dh_f32) {
-                reinterpret_cast<float*>(p.dH)[slot * p.d + n] = acc[i][j][e];
-              } else {
-                reinterpret_cast<__bf16*>(p.dH)[slot * p.d + n] = (__bf16)acc[i][j][e];
-              }
+            for (int j = 0; j < 8; ++j) {
+              const int n = ncol_base + j * 16;
+              if (n < p.d) row[n] = acc[i][j][e];
             }
           }
         }
+    } else {
+      // stage the tile as bf16 in LDS, [token][hidden], then 32 lanes store one 512-byte row segment
+      __bf16* st = reinterpret_cast<__bf16*>(smem);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            st[(wm * 128 + i * 16 + 4 * fq + e) * STASH_LD + wn * 128 + j * 16 + frow] = (__bf16)acc[i][j][e];
+      __syncthreads();
+#pragma unroll 4
+      for (int k = 0; k < 32; ++k) {
+        const int c = tid + NTHREADS * k;
+        const int row = c >> 5, col = c & 31;
+        if (m0 + row < M && n0 + col * 8 < p.d) {
+          const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * (STASH_LD * 2) + col * 16);
+          *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.dH) + (int64_t)p.row_index[m0 + row] * p.d + n0 + col * 8) = v;
+        }
       }
+    }
   } else {
     // rows = vocabulary ids, cols = hidden index; fp32 accumulate into dW.  The old values of
-    // one 32-row band are fetched as a batch before any store, so their latencies overlap.
+    // one 16-row band are fetched as a batch before any store, so their latencies overlap.
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float old[4][16];
+    for (int i = 0; i < 8; ++i) {
+      float old[8][4];
       if (!p.overwrite) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int v = mrow_base + i * 32 + 8 * (e >> 2) + (e & 3);
+        for (int e = 0; e < 4; ++e) {
+          const int v = mrow_base + i * 16 + e;
           const float* row = p.dW + (int64_t)(v < p.V ? v : p.V - 1) * p.d;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int n = ncol_base + j * 32;
+          for (int j = 0; j < 8; ++j) {
+            const int n = ncol_base + j * 16;
             old[j][e] = row[n < p.d ? n : p.d - 1];
           }
         }
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int v = mrow_base + i * 32 + 8 * (e >> 2) + (e & 3);
+      for (int e = 0; e < 4; ++e) {
+        const int v = mrow_base + i * 16 + e;
         if (v < p.V) {
           float* row = p.dW + (int64_t)v * p.d;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int n = ncol_base + j * 32;
+          for (int j = 0; j < 8; ++j) {
+            const int n = ncol_base + j * 16;
             if (n < p.d) row[n] = p.overwrite ? acc[i][j][e] : old[j][e] + acc[i][j][e];
           }
         }
