@@ -170,6 +170,14 @@ def main():
     classes = {k: dict(ms_per_step=round(v[0] / args.steps, 3), launches_per_step=v[1] / args.steps)
                for k, v in prof.items()}
 
+    # what the matrix cores sustain on this machine with no memory traffic: clock-limited (constant
+    # operands) and power-limited (random-mantissa operands, like the workload's tensors)
+    measured_peak = dict(unit="TFLOP/s", instruction="v_mfma_f32_16x16x32_bf16, registers only, 0.5 s each",
+                         constant_operands=round(mrl.probe_mfma_rate(False, 0.5), 1),
+                         random_operands=round(mrl.probe_mfma_rate(True, 0.5), 1))
+    measured_peak["pct_of_random_operand_rate"] = round(
+        100.0 * tokens_per_s * flop_per_token / (measured_peak["random_operands"] * 1e12), 2)
+
     base = None
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
@@ -182,7 +190,7 @@ def main():
                             V=V, d=d, B=B, T=T, slots=N, scored_tokens=n_scored, prompts=sp.n_prompts,
                             rollouts_per_prompt=sp.k_own + sp.k_peer),
                 pct_bf16_mfma_peak=round(pct_peak, 2), flop_per_token=flop_per_token,
-                roofline=roofline, kernel_classes=classes, cpu_baseline=base,
+                roofline=roofline, measured_mfma_peak=measured_peak, kernel_classes=classes, cpu_baseline=base,
                 loss=dict(total=stats["loss_total"], clip_frac=stats["n_clipped_tokens"] / max(n_scored, 1),
                           mean_ratio=stats["mean_ratio"]))
     print(json.dumps(line), flush=True)

@@ -211,6 +211,22 @@ enum {
 int mrl_profile_enable(int on);
 int mrl_profile_collect(double* ms_per_class /*host*/, int64_t* launches_per_class /*host*/);
 
+/* ------------------------------------------------------------------------
+ * Diagnostic: sustained rate of the matrix cores on the MFMA instruction the
+ * GEMM kernels use (bf16 16x16x32, fp32 accumulate), registers only, no memory
+ * traffic.  random_operands = 0: constant operands (clock-limited peak);
+ * 1: random sign / mantissa operands, which is what activations and weights
+ * look like - the device lowers its clock under the higher switching power, so
+ * this is the ceiling of any bf16 GEMM on real data.  Benchmarks print both
+ * next to the published peak (Sec. 3 defines the contraction this bounds).
+ * Synchronous: runs on the null stream for about `seconds` (0 < seconds <= 5)
+ * and waits.  scratch: device memory, at least 1024 bytes per compute unit
+ * (512 KiB is enough for any device); out_tflops: host.  Errors: MRL_ERR_NULL,
+ * MRL_ERR_CONFIG (seconds), MRL_ERR_WORKSPACE (scratch too small), MRL_ERR_DEVICE.
+ * ---------------------------------------------------------------------- */
+int mrl_probe_mfma_rate(int32_t random_operands, double seconds, void* scratch /*dev*/,
+                        size_t scratch_bytes, double* out_tflops /*host*/);
+
 #ifdef __cplusplus
 }
 #endif

@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
     L.mrl_profile_enable.argtypes = [c_int]
     L.mrl_profile_collect.restype = c_int
     L.mrl_profile_collect.argtypes = [POINTER(c_double), POINTER(c_int64)]
+    L.mrl_probe_mfma_rate.restype = c_int
+    L.mrl_probe_mfma_rate.argtypes = [c_int32, c_double, c_void_p, c_size_t, POINTER(c_double)]
     _LIB = L
     return L
 
@@ -238,3 +240,13 @@ def profile_collect() -> dict:
     n = (c_int64 * len(PROF_CLASSES))()
     _check(lib().mrl_profile_collect(ms, n), "mrl_profile_collect")
     return {name: (ms[i], n[i]) for i, name in enumerate(PROF_CLASSES)}
+
+
+def probe_mfma_rate(random_operands: bool, seconds: float = 0.5, device="cuda:0") -> float:
+    """TFLOP/s the matrix cores sustain on the GEMM kernels' MFMA instruction, registers only."""
+    scratch = torch.empty(512 * 1024, dtype=torch.uint8, device=device)
+    out = c_double(0.0)
+    torch.cuda.synchronize()
+    _check(lib().mrl_probe_mfma_rate(1 if random_operands else 0, float(seconds), _ptr(scratch),
+                                     scratch.numel(), ctypes.byref(out)), "mrl_probe_mfma_rate")
+    return out.value

@@ -178,15 +178,16 @@ void forward_chunk(const void* H, const void* W, int d, int V, bool bf16, const 
                    int64_t c0, bool stash, hipStream_t s) {
   const int32_t* row_index = at<int32_t>(ws, L.row_index);
   const int64_t* n_scored = at<int64_t>(ws, L.counters);
-  Scope sc(MRL_PROF_GEMM_FWD, s);
   if (bf16) {
     for (int sub = 0; sub < L.chunk_rows; sub += kFwdSubChunk) {
       const int rows = L.chunk_rows - sub < kFwdSubChunk ? L.chunk_rows - sub : kFwdSubChunk;
+      Scope sc(MRL_PROF_GEMM_FWD, s);   // one event pair per kernel launch
       launch_gemm_fwd_bf16(W, H, row_index, n_scored, c0 + sub, rows, V, d, at<float>(ws, L.part_max) + sub,
                            at<float>(ws, L.part_sum) + sub, L.chunk_rows,
                            stash ? at<uint16_t>(ws, L.Z) + (size_t)sub * L.ldz : nullptr, L.ldz, s);
     }
   } else {
+    Scope sc(MRL_PROF_GEMM_FWD, s);
     GemmF32Args g = {};
     g.A = static_cast<const float*>(H); g.lda = d; g.a_rows = row_index + c0;
     g.B = static_cast<const float*>(W); g.ldb = d;

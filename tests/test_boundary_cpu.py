@@ -134,3 +134,12 @@ def test_profile_calls_without_device():
     assert m.lib().mrl_profile_collect(None, None) == -1
     out = m.profile_collect()
     assert set(out) == set(m.PROF_CLASSES)
+
+
+def test_probe_argument_errors():
+    f = m.lib().mrl_probe_mfma_rate
+    out = ctypes.c_double(0.0)
+    assert f(0, 0.1, None, 1 << 20, ctypes.byref(out)) == -1
+    assert f(0, 0.1, FAKE, 1 << 20, None) == -1
+    assert f(0, 0.0, FAKE, 1 << 20, ctypes.byref(out)) == -7
+    assert f(0, 60.0, FAKE, 1 << 20, ctypes.byref(out)) == -7

@@ -225,3 +225,12 @@ def test_group_advantages_defaults_and_orphans(mrl):
     a2, *_ = orc.group_advantages(r.cpu().numpy()[:5].astype(np.float64), gid.cpu().numpy()[:5], 3, None,
                                   own.cpu().numpy()[:5], own.cpu().numpy()[:5], mix_alpha=0.2)
     assert np.allclose(adv2.cpu().numpy()[:5], a2, atol=1e-6)
+
+
+def test_mfma_rate_probe(mrl):
+    """The diagnostic runs and reports a plausible rate; random operands never beat constant ones by much."""
+    const = mrl.probe_mfma_rate(False, 0.05)
+    rnd = mrl.probe_mfma_rate(True, 0.05)
+    assert 300.0 < const < 2600.0, const
+    assert 300.0 < rnd < 2600.0, rnd
+    assert rnd < 1.05 * const
