@@ -75,7 +75,7 @@ struct Layout {
   size_t counters, row_index, block_counts, zt, part_max, part_sum;
   size_t seq_len, seq_coef, group_count, lse_c, g_c, loss_partials, Z, Pt, Ht, Wt;
   int chunk_rows = 0, n_partials = 0;
-  int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of Z/P and Wt, ldr: of Pt and Ht
+  int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of Z/P and Wt, ldr: of Ht (and the fp32 path's Pt)
   int64_t epi_blocks_total = 0;
 };
 
@@ -114,7 +114,7 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
     L.g_c = take(off, (size_t)(N + 1) * 4);
     L.loss_partials = take(off, (size_t)(L.epi_blocks_total + 1) * 10 * 8);
     L.Z = take(off, (size_t)chunk_rows * L.ldz * es);
-    L.Pt = take(off, (size_t)L.Vp * L.ldr * es);
+    L.Pt = bf16 ? 0 : take(off, (size_t)L.Vp * L.ldr * es);   // fp32 path only: the bf16 dW GEMM reads P itself
     L.Ht = take(off, (size_t)d * L.ldr * es);
     L.Wt = take(off, (size_t)d * L.ldz * es);
   } else if (!bf16) {
@@ -411,7 +411,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     if (!bwd) continue;
     {
       Scope sc(MRL_PROF_CONVERT, s);
-      launch_convert(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Pt), L.ldr, at<float>(ws, L.lse_c),
+      launch_convert(at<void>(ws, L.Z), L.ldz, bf16 ? nullptr : at<void>(ws, L.Pt), L.ldr, at<float>(ws, L.lse_c),
                      at<float>(ws, L.g_c), target_ids, row_index, n_scored, c0, L.chunk_rows, V, (int)L.Vp,
                      bf16, s);
       if (out_dW)
@@ -438,7 +438,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
       Scope sc(MRL_PROF_GEMM_DW, s);
       const int overwrite = (c == 0 && !cfg->accumulate_dw) ? 1 : 0;
       if (bf16) {
-        launch_gemm_dw_bf16(at<void>(ws, L.Pt), L.ldr, at<void>(ws, L.Ht), L.ldr, n_scored, c0,
+        launch_gemm_dw_bf16(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Ht), L.ldr, n_scored, c0,
                             L.chunk_rows, V, d, out_dW, overwrite, s);
       } else {
         GemmF32Args g = {};

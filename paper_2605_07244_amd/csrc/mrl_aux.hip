@@ -445,37 +445,42 @@ __global__ __launch_bounds__(256) void k_finalize(const double* parts, int64_t n
 }
 
 // ----------------------------------------------------------------------------
-// dz conversion, bf16 path.  Tile = 64 rows x 256 columns per block.
-//   in : fp16 logits z[i][v]            (in place)
-//   out: bf16 P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)), and Pt[v][i]
+// dz conversion, bf16 path (proof of Prop. 4: grad log pi(a_i) = e_i - pi).  Elementwise and
+// in place: fp16 logits z[i][v] -> bf16 P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)).
+// A block converts CV_ROWS rows x 2048 columns, 16 bytes per thread and row.  Rows from the
+// valid count up to its multiple of 64 and columns from V up to Vp are written as zeros
+// (the dW contraction runs over whole 64-row panels, the dH one over whole 256-column tiles).
 // ----------------------------------------------------------------------------
-constexpr int CV_ROWS = 64, CV_COLS = 256, CV_LD = CV_COLS + 8;
-
-__global__ __launch_bounds__(256) void k_convert_bf16(uint16_t* ZP, int64_t ldz, uint16_t* Pt, int64_t ldpt,
-                                                      const float* lse_c, const float* g_c,
-                                                      const int32_t* targets, const int32_t* row_index,
-                                                      const int64_t* n_scored, int64_t chunk_start,
-                                                      int chunk_rows, int V) {
-  __shared__ __attribute__((aligned(16))) uint16_t tile[CV_ROWS * CV_LD];
+constexpr int CV_ROWS = 8, CV_COLS = 2048;
+__global__ __launch_bounds__(256) void k_convert_bf16(uint16_t* ZP, int64_t ldz, const float* lse_c,
+                                                      const float* g_c, const int32_t* targets,
+                                                      const int32_t* row_index, const int64_t* n_scored,
+                                                      int64_t chunk_start, int chunk_rows, int V, int Vp) {
   const int nvalid = valid_rows(n_scored, chunk_start, chunk_rows);
-  const int i0 = blockIdx.y * CV_ROWS, v0 = blockIdx.x * CV_COLS;
-  if (i0 >= (nvalid + 63) / 64 * 64) return;
-  const int c = threadIdx.x & 31;   // 16-byte chunk (8 columns)
-  const int r = threadIdx.x >> 5;   // 0..7
+  const int nzero = (nvalid + 63) / 64 * 64 < chunk_rows ? (nvalid + 63) / 64 * 64 : chunk_rows;
+  const int i0 = blockIdx.y * CV_ROWS;
+  if (i0 >= nzero) return;
+  const int vbase = blockIdx.x * CV_COLS + threadIdx.x * 8;
+  if (vbase >= Vp) return;
   constexpr float LOG2E = 1.4426950408889634f;
+  uint4 zin[CV_ROWS];
 #pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const int row = r + 8 * k;
-    const int i = i0 + row;
+  for (int k = 0; k < CV_ROWS; ++k) {
+    const int i = i0 + k;
+    zin[k] = make_uint4(0, 0, 0, 0);
+    if (i < nvalid) zin[k] = *reinterpret_cast<const uint4*>(ZP + (int64_t)i * ldz + vbase);
+  }
+#pragma unroll
+  for (int k = 0; k < CV_ROWS; ++k) {
+    const int i = i0 + k;
+    if (i >= nzero) break;
     uint4 outv = make_uint4(0, 0, 0, 0);
     if (i < nvalid) {
       const int64_t ci = chunk_start + i;
       const float lse2 = lse_c[ci] * LOG2E;
       const float g = g_c[ci];
       const int y = targets[row_index[ci]];
-      uint16_t* src = ZP + (int64_t)i * ldz + v0 + c * 8;
-      const uint4 zin = *reinterpret_cast<const uint4*>(src);
-      const uint32_t zw[4] = {zin.x, zin.y, zin.z, zin.w};
+      const uint32_t zw[4] = {zin[k].x, zin[k].y, zin[k].z, zin[k].w};
       uint32_t ow[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
@@ -485,9 +490,9 @@ __global__ __launch_bounds__(256) void k_convert_bf16(uint16_t* ZP, int64_t ldz,
           const uint16_t hb = (uint16_t)(h ? (zw[q] >> 16) : (zw[q] & 0xffffu));
           _Float16 hf;
           __builtin_memcpy(&hf, &hb, 2);
-          const int v = v0 + c * 8 + q * 2 + h;
+          const int v = vbase + q * 2 + h;
           const float p = __builtin_amdgcn_exp2f(fmaf((float)hf, LOG2E, -lse2));
-          float val = g * ((v == y ? 1.f : 0.f) - p);
+          const float val = g * ((v == y ? 1.f : 0.f) - p);
           pv[h] = v < V ? val : 0.f;
         }
         const __bf16 b0 = (__bf16)pv[0], b1 = (__bf16)pv[1];
@@ -497,25 +502,8 @@ __global__ __launch_bounds__(256) void k_convert_bf16(uint16_t* ZP, int64_t ldz,
         ow[q] = (uint32_t)u0 | ((uint32_t)u1 << 16);
       }
       outv = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-      *reinterpret_cast<uint4*>(src) = outv;
     }
-    *reinterpret_cast<uint4*>(&tile[row * CV_LD + c * 8]) = outv;
-  }
-  __syncthreads();
-  // transposed write: Pt[v0 + vv][i0 .. i0 + 64): 8 chunks of 8 rows per column
-  const int rc = threadIdx.x & 7;    // row chunk
-  const int vb = threadIdx.x >> 3;   // 0..31
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const int vv = vb + 32 * k;
-    uint32_t ow[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const uint32_t lo = tile[(rc * 8 + q * 2) * CV_LD + vv];
-      const uint32_t hi = tile[(rc * 8 + q * 2 + 1) * CV_LD + vv];
-      ow[q] = lo | (hi << 16);
-    }
-    *reinterpret_cast<uint4*>(Pt + (int64_t)(v0 + vv) * ldpt + i0 + rc * 8) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    *reinterpret_cast<uint4*>(ZP + (int64_t)i * ldz + vbase) = outv;
   }
 }
 
@@ -671,10 +659,9 @@ void launch_convert(void* ZP, int64_t ldz, void* Pt, int64_t ldpt, const float* 
                     const int64_t* n_scored, int64_t chunk_start, int chunk_rows, int V, int Vp,
                     int is_bf16, hipStream_t stream) {
   if (is_bf16) {
-    dim3 grid(Vp / CV_COLS, chunk_rows / CV_ROWS);
+    dim3 grid((Vp + CV_COLS - 1) / CV_COLS, (chunk_rows + CV_ROWS - 1) / CV_ROWS);
     hipLaunchKernelGGL(k_convert_bf16, grid, dim3(256), 0, stream, static_cast<uint16_t*>(ZP), ldz,
-                       static_cast<uint16_t*>(Pt), ldpt, lse_c, g_c, targets, row_index, n_scored,
-                       chunk_start, chunk_rows, V);
+                       lse_c, g_c, targets, row_index, n_scored, chunk_start, chunk_rows, V, Vp);
   } else {
     int gx = (V + 255) / 256; gx = gx > 64 ? 64 : gx;
     dim3 grid(gx, chunk_rows);

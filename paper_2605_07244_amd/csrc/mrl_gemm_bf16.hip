@@ -23,7 +23,8 @@
 //        the M side makes the max / sum-exp reduction over the vocabulary an
 //        in-register reduction with two cross-lane steps.
 //   DH : A = dz rows (tokens), B = W^T;  rows are scattered to the padded slots.
-//   DW : A = dz^T (vocabulary rows), B = H^T; fp32 read-modify-write of dW.
+//   DW : A = dz^T, read from the dz rows themselves (K-major panel, transposing LDS
+//        reads), B = H^T; fp32 read-modify-write of dW.
 #include "mrl_internal.h"
 
 namespace mrl {
@@ -38,6 +39,9 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
 #ifndef LD_GROUPS
 #define LD_GROUPS 8         // MFMA groups (of 16 per K panel) over which a panel's 16 direct loads are spread
+#endif
+#ifndef RD_GROUPS
+#define RD_GROUPS 7         // MFMA groups (after the first) over which the 8 fragment pairs of the next K step are read
 #endif
 #ifndef PF_DIST
 #define PF_DIST 3           // L2 prefetch distance in K panels (0 = off)
@@ -117,6 +121,9 @@ __device__ inline bool tile_coords(int bid, int Mt, int Nt, int& tm, int& tn, in
   return tm < Mt && tn < Nt;
 }
 
+// swizzle of the K-major A panel: rows k, k+1, k+2, k+3 and k+8 (or k+16) get distinct values
+__device__ inline int kswz(int k) { return (k & 3) | ((((k >> 3) ^ (k >> 4)) & 1) << 2); }
+
 __device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // The MFMA is issued through inline assembly with the accumulator tied in place in an
@@ -170,9 +177,16 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M || n0 >= N) return;
 
-  // ---- global -> LDS: one direct load moves 8 rows x 128 B (1 KB, contiguous in LDS).
-  // Wave w owns row blocks 8w .. 8w+7 of each operand panel; lane l fills LDS chunk
-  // (row l/8, slot l%8) and therefore fetches logical chunk slot ^ ((row >> 1) & 7).
+  // ---- global -> LDS: one direct load moves 1 KB, contiguous in LDS.
+  // Row-major operands ([row][k], k contiguous): 8 rows x 128 B per load.  Wave w owns row
+  // blocks 8w .. 8w+7 of each operand panel; lane l fills LDS chunk (row l/8, slot l%8) and
+  // therefore fetches logical chunk slot ^ ((row >> 1) & 7).
+  // K-major A operand (DW: A[m][k] = dz[k][m], stored as token rows with the vocabulary
+  // contiguous): the panel is 64 k rows x 512 B and a load moves 2 of them; lane l fills chunk
+  // slot l%32 of row l/32 and fetches logical chunk slot ^ (h(k) << 1), the swizzle that makes
+  // the transposing fragment reads below conflict-free.
+  constexpr bool A_KMAJOR = (MODE == MODE_DW);
+  const int64_t a_kstep = A_KMAJOR ? (int64_t)BK * p.lda : BK;   // elements per K panel
   const int lrow = lane >> 3;
   const uint16_t* a_ptr[8];
   const uint16_t* b_ptr[8];
@@ -184,7 +198,12 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     int rb = n0 + r; rb = rb < N ? rb : N - 1;
     int64_t rowa = ra, rowb = rb;
     if (MODE == MODE_FWD) rowb = p.row_index[rb];
-    a_ptr[i] = p.A + rowa * p.lda + lchunk * 8;
+    if (A_KMAJOR) {
+      const int k = 2 * (wave * 8 + i) + (lane >> 5);  // k row within the panel
+      a_ptr[i] = p.A + (int64_t)k * p.lda + m0 + (((lane & 31) ^ (kswz(k) << 1)) << 3);
+    } else {
+      a_ptr[i] = p.A + rowa * p.lda + lchunk * 8;
+    }
     b_ptr[i] = p.B + rowb * p.ldb + lchunk * 8;
   }
   // The direct load is issued through inline assembly on purpose: the compiler's wait-count
@@ -205,7 +224,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     const int koff = kt * BK;
 #pragma unroll
     for (int i = i0; i < i0 + n; ++i) {
-      load_lds16(a_ptr[i] + koff, st + i * 1024);
+      load_lds16(a_ptr[i] + kt * a_kstep, st + i * 1024);
       load_lds16(b_ptr[i] + koff, st + TILE_BYTES + i * 1024);
     }
   };
@@ -221,8 +240,13 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   {
     int r;
     if ((wave & 1) == 0) {
-      r = m0 + ((sn + wave) & 3) * 64 + lane; r = r < M ? r : M - 1;
-      pf_ptr = p.A + (int64_t)r * p.lda;
+      r = ((sn + wave) & 3) * 64 + lane;
+      if (A_KMAJOR) {                    // 64 k rows of four 128-byte lines
+        pf_ptr = p.A + (int64_t)(r >> 2) * p.lda + m0 + (r & 3) * 64;
+      } else {
+        r += m0; r = r < M ? r : M - 1;
+        pf_ptr = p.A + (int64_t)r * p.lda;
+      }
     } else {
       r = n0 + ((sm + (wave - 1) + 4 * (lane >> 5)) & 7) * 32 + (lane & 31); r = r < N ? r : N - 1;
       int64_t rowb = r;
@@ -230,10 +254,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       pf_ptr = p.B + rowb * p.ldb;
     }
   }
+  const int64_t pf_kstep = (wave & 1) == 0 ? a_kstep : (int64_t)BK;
   const uint32_t pf_lds = __builtin_amdgcn_readfirstlane(lds_base + PIPE_BYTES + wave * 256);
   auto prefetch = [&](int kt) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(pf_ptr + kt * BK), "s"(pf_lds) : "memory");
+                 :: "v"(pf_ptr + kt * pf_kstep), "s"(pf_lds) : "memory");
   };
 
   // ---- fragment read offsets.  A 16x16x32 operand fragment: lane -> row (lane & 15),
@@ -248,6 +273,33 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     a_off[ks] = (wm * 128 + frow) * 128 + (chunk << 4);
     b_off[ks] = TILE_BYTES + (wn * 128 + frow) * 128 + (chunk << 4);
   }
+
+  // K-major A panel: the transposing LDS read hands lane (g = lane / 16, s = lane % 16) the four
+  // k values kb .. kb+3 of column m = mb + s when lane s points at row kb + s/4, columns
+  // mb + 4*(s%4) .. +3.  Two of them (kb = 8g and 8g + 4 within the K step) make the lane's
+  // 8-element fragment.  A 64-bit read is served 32 lanes per cycle: 8 rows x 32 bytes, and the
+  // swizzle h(k) moves the 32-byte column groups of those rows to distinct bank windows.
+  int a_tr_base = 0;
+  if (A_KMAJOR) {
+    const int k = 8 * fq + (frow >> 2);
+    a_tr_base = k * 512 + wm * 256 + (kswz(k) << 5) + ((frow & 2) << 3) + ((frow & 1) << 3);
+  }
+  auto read_a = [&](int st, int ks, int ib) -> bf16x8 {
+#ifdef PROBE_TRASB128
+    if (false) {
+#else
+    if (A_KMAJOR) {
+#endif
+      typedef short v4i16 __attribute__((ext_vector_type(4)));
+      typedef short v8i16 __attribute__((ext_vector_type(8)));
+      typedef __attribute__((address_space(3))) v4i16* lds_v4i16;
+      unsigned char* q = smem + st + (a_tr_base ^ (ib << 5)) + ks * 16384;
+      const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)q);
+      const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(q + 2048));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+    return *reinterpret_cast<const bf16x8*>(smem + st + a_off[ks] + ib * 2048);
+  };
 
   f32x4 acc[8][8];
 #pragma unroll
@@ -277,7 +329,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       if (j * LD_GROUPS / 16 == g) {
         const uint32_t st = slot * STAGE_BYTES + wave_lds + (j >> 1) * 1024;
         if (j & 1) load_lds16(b_ptr[j >> 1] + kt * BK, st + TILE_BYTES);
-        else load_lds16(a_ptr[j >> 1] + kt * BK, st);
+        else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st);
       }
   };
   // one K step: multiply fragments (ca, cb); meanwhile read K step ks_next of the panel at LDS
@@ -286,9 +338,17 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
                    int kt_load, int slot_load, int g0, int kt_pre) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+      // fragment reads of the next K step: none in the first group (the wait for the current
+      // fragments sits there and would otherwise cover fresh reads as well), then pair r in
+      // group 1 + r * RD_GROUPS / 8, so that the last ones are issued several groups before
+      // the wait that precedes their use
       if (ks_next >= 0) {
-        PROBE_RD(na[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[ks_next & 1] + i * 2048));
-        PROBE_RD(nb[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks_next & 1] + i * 2048));
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+          if (1 + r * RD_GROUPS / 8 == i) {
+            PROBE_RD(na[r] = read_a(st, ks_next & 1, r));
+            PROBE_RD(nb[r] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks_next & 1] + r * 2048));
+          }
       }
 #pragma unroll
       for (int j = 0; j < 8; ++j)
@@ -304,7 +364,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   auto read_frags = [&](bf16x8* af, bf16x8* bfr, int st, int ks) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      af[i] = *reinterpret_cast<const bf16x8*>(smem + st + a_off[ks] + i * 2048);
+      af[i] = read_a(st, ks, i);
       bfr[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks] + i * 2048);
     }
   };
@@ -535,11 +595,11 @@ void launch_gemm_dh_bf16(const void* P, int64_t ldp, const void* Wt, int64_t ldw
   launch<MODE_DH>(p, stream);
 }
 
-void launch_gemm_dw_bf16(const void* Pt, int64_t ldpt, const void* Ht, int64_t ldht,
+void launch_gemm_dw_bf16(const void* P, int64_t ldp, const void* Ht, int64_t ldht,
                          const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
                          int V, int d, float* dW, int overwrite, hipStream_t stream) {
   Params p = {};
-  p.A = static_cast<const uint16_t*>(Pt); p.lda = ldpt; p.M = (int)round_up(V, kTile);
+  p.A = static_cast<const uint16_t*>(P); p.lda = ldp; p.M = (int)round_up(V, kTile);
   p.B = static_cast<const uint16_t*>(Ht); p.ldb = ldht; p.N = d;
   p.K = chunk_rows;
   p.n_scored = n_scored; p.chunk_start = chunk_start; p.chunk_rows = chunk_rows;

@@ -34,9 +34,10 @@ void launch_gemm_dh_bf16(const void* P, int64_t ldp, const void* Wt, int64_t ldw
                          const int32_t* row_index, const int64_t* n_scored, int64_t chunk_start,
                          int chunk_rows, int Vp, int d, void* dH, int dh_f32, hipStream_t stream);
 
-// dW: A = Pt [Vp, chunk_rows], B = Ht [d, chunk_rows]; dW[v, :] = (or +=) sum over the
+// dW: A = P^T read in place from P [chunk_rows, Vp] (rows >= valid rows rounded up to 64 and
+// columns >= V must be zero), B = Ht [d, chunk_rows]; dW[v, :] = (or +=) sum over the
 // chunk's valid rows.  overwrite = 1 stores, 0 adds into the existing values.
-void launch_gemm_dw_bf16(const void* Pt, int64_t ldpt, const void* Ht, int64_t ldht,
+void launch_gemm_dw_bf16(const void* P, int64_t ldp, const void* Ht, int64_t ldht,
                          const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
                          int V, int d, float* dW, int overwrite, hipStream_t stream);
 
@@ -104,8 +105,9 @@ int row_epilogue_blocks(int chunk_rows);
 void launch_row_epilogue(const RowEpiArgs& a, hipStream_t stream);
 
 // dz conversion: reads the chunk's logits (fp16 for the bf16 path, float for fp32),
-// writes P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)) in place (same element size)
-// and the transpose Pt[v][i]; rows >= valid rows and columns >= V become zero.
+// writes P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)) in place (same element size); rows from
+// the valid count up to its multiple of 64 and columns >= V become zero.  The fp32 path also
+// writes the transpose Pt[v][i] (Pt is unused, and may be null, for bf16).
 void launch_convert(void* ZP, int64_t ldz, void* Pt, int64_t ldpt, const float* lse_c,
                     const float* g_c, const int32_t* targets, const int32_t* row_index,
                     const int64_t* n_scored, int64_t chunk_start, int chunk_rows, int V, int Vp,
