@@ -169,6 +169,22 @@ def main():
                     flops_per_launch=flops_per_launch)
     classes = {k: dict(ms_per_step=round(v[0] / args.steps, 3), launches_per_step=v[1] / args.steps)
                for k, v in prof.items()}
+    # HBM-bound passes: algorithmic bytes per step / measured time of the class
+    Vp = (V + 255) // 256 * 256
+    n_part = 2 * (Vp // 256)
+    alg_bytes = dict(
+        # mask + target scans (count, fill, sequence lengths), row index, zero fill of the unscored
+        # slots' dH rows and log-probs, target logits (one H row and one W row per scored token)
+        prep=3 * N * 5 + 4 * n_scored + (N - n_scored) * (2 * d + 4) + n_scored * (4 * d + 12),
+        adv=B * 22 + G * 9,
+        # (max, sum-exp) partials and the per-token inputs / outputs of Eq. (1)
+        row_epilogue=n_scored * (8 * n_part + 32),
+        # fp16 logits in, bf16 dz out, plus the transposed copy of the pass's hidden rows
+        convert=n_scored * (4 * Vp + 4 * d))
+    hbm_passes = {k: dict(algorithmic_GB=round(b / 1e9, 3),
+                          achieved_GBps=round(b * args.steps / (prof[k][0] * 1e-3) / 1e9, 1) if prof[k][0] > 0 else None,
+                          peak_GBps=8000.0)
+                  for k, b in alg_bytes.items()}
 
     # what the matrix cores sustain on this machine with no memory traffic: clock-limited (constant
     # operands) and power-limited (random-mantissa operands, like the workload's tensors)
@@ -190,7 +206,8 @@ def main():
                             V=V, d=d, B=B, T=T, slots=N, scored_tokens=n_scored, prompts=sp.n_prompts,
                             rollouts_per_prompt=sp.k_own + sp.k_peer),
                 pct_bf16_mfma_peak=round(pct_peak, 2), flop_per_token=flop_per_token,
-                roofline=roofline, measured_mfma_peak=measured_peak, kernel_classes=classes, cpu_baseline=base,
+                roofline=roofline, measured_mfma_peak=measured_peak, kernel_classes=classes,
+                hbm_passes=hbm_passes, cpu_baseline=base,
                 loss=dict(total=stats["loss_total"], clip_frac=stats["n_clipped_tokens"] / max(n_scored, 1),
                           mean_ratio=stats["mean_ratio"]))
     print(json.dumps(line), flush=True)
