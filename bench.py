@@ -63,6 +63,42 @@ def cpu_baseline(batch, sp, rows_T=256):
                        f"fp64 NumPy, {dt:.1f} s")
 
 
+def thl_alignment_leg(mrl, synth, torch, with_cpu, B=2048, S_src=1180, S_tgt=1536, reps=20):
+    """The word-level trace alignment of the pooled peer rollouts (a pass of its own, before the
+    scoring step, not part of `value`): achieved GB/s on algorithmic bytes, oracle on a sample."""
+    b = synth.make_thl(B, S_src, S_tgt)
+    call = lambda: mrl.thl_word_align(b["src_logp"], b["src_mask"], b["src_word_map"], b["src_map_len"],
+                                      b["tgt_mask"], b["tgt_word_map"], b["tgt_map_len"], b["max_words"],
+                                      want_bad_count=False)
+    call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    # log-prob, mask byte and map entry per source position; mask byte, map entry and output per target position
+    nbytes = B * (S_src * 9 + S_tgt * 9)
+    n_tok = int(b["tgt_mask"].sum().item())
+    leg = dict(workload=f"{B} peer rollouts, source grid {S_src}, target grid {S_tgt} (configuration 3 lengths)",
+               ms_per_launch=round(ms, 4), algorithmic_MB=round(nbytes / 1e6, 2),
+               achieved_GBps=round(nbytes / (ms * 1e-3) / 1e9, 1), peak_GBps=8000.0,
+               target_tokens_per_s=round(n_tok / (ms * 1e-3), 1))
+    if with_cpu:
+        from oracle import thl_oracle
+        n = 64
+        c = {k: (v[:n].cpu().numpy() if isinstance(v, torch.Tensor) else v) for k, v in b.items()}
+        t0 = time.perf_counter()
+        thl_oracle.word_align_logprobs(c["src_logp"].astype("float64"), c["src_mask"], c["src_word_map"], c["src_map_len"],
+                                       c["tgt_mask"], c["tgt_word_map"], c["tgt_map_len"], -100.0)
+        dt = time.perf_counter() - t0
+        leg["cpu_oracle"] = dict(target_tokens_per_s=round(int(c["tgt_mask"].sum()) / dt, 1), cores=1,
+                                 sample=f"first {n} sequences, pure Python, {dt:.2f} s")
+    return leg
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,6 +230,8 @@ def main():
     measured_peak["pct_of_random_operand_rate"] = round(
         100.0 * tokens_per_s * flop_per_token / (measured_peak["random_operands"] * 1e12), 2)
 
+    thl_leg = thl_alignment_leg(mrl, synth, torch, with_cpu=not args.no_cpu_baseline)
+
     base = None
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
@@ -207,7 +245,7 @@ def main():
                             rollouts_per_prompt=sp.k_own + sp.k_peer),
                 pct_bf16_mfma_peak=round(pct_peak, 2), flop_per_token=flop_per_token,
                 roofline=roofline, measured_mfma_peak=measured_peak, kernel_classes=classes,
-                hbm_passes=hbm_passes, cpu_baseline=base,
+                hbm_passes=hbm_passes, thl_word_align=thl_leg, cpu_baseline=base,
                 loss=dict(total=stats["loss_total"], clip_frac=stats["n_clipped_tokens"] / max(n_scored, 1),
                           mean_ratio=stats["mean_ratio"]))
     print(json.dumps(line), flush=True)

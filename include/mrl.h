@@ -212,6 +212,44 @@ int mrl_profile_enable(int on);
 int mrl_profile_collect(double* ms_per_class /*host*/, int64_t* launches_per_class /*host*/);
 
 /* ------------------------------------------------------------------------
+ * (4) THL word-level trace alignment on integer word maps (Sec. 4.3; App. D,
+ *     "THL WordAlignLogProbs", Alg. 2).  A peer's per-token log-probs on its own
+ *     token grid (source) are carried over to the learner's grid (target): the
+ *     source log-probs of the response tokens of a word are summed (Z_w) and every
+ *     target response token of that word receives Z_w / C_w, C_w being the number
+ *     of target tokens of the word.  The result is the behaviour trace of a pooled
+ *     peer rollout (behav_logp of call (3)); positions left at ignore_value are
+ *     the ones the caller clears in token_mask.
+ *
+ *   src_logp     [B, S_src] float, finite, |value| < 2^30.
+ *   src_mask     [B, S_src] 1 = response token of the source grid.
+ *   src_word_map [B, S_src] entry p of row i is the word index, in [0, max_words),
+ *                of the p-th response token (the p-th set bit of src_mask row i), or
+ *                -1 for a token that belongs to no word (leading delimiters); only
+ *                the first src_map_len[i] entries are meaningful.
+ *   src_map_len  [B] length of row i's map.  When it differs from the number of
+ *                response tokens, the shorter of the two is used (Alg. 2).
+ *   tgt_*        likewise on the target grid.
+ *   out          [B, S_tgt] fully overwritten: ignore_value everywhere except at the
+ *                target response tokens that carry a word.  A word without source
+ *                tokens has Z_w = 0.  A sequence whose source side carries no word at
+ *                all stays entirely at ignore_value.
+ *   out_bad_words [1] | NULL: number of map entries outside [-1, max_words) among the
+ *                entries in use; they are treated as -1.
+ *   max_words <= 8192 (per-word sums and counts live in on-chip memory).
+ *   Sums are accumulated exactly in 2^-32 fixed point: results do not depend on the
+ *   order of evaluation and are bit-reproducible.  No workspace.  Asynchronous on
+ *   `stream`.  All tensor pointers are device pointers owned by the caller.
+ *   Errors: MRL_ERR_SHAPE (sizes, max_words), MRL_ERR_NULL.
+ * ---------------------------------------------------------------------- */
+int mrl_thl_word_align(const float* src_logp /*[B,S_src] dev*/, const uint8_t* src_mask /*[B,S_src] dev*/,
+                       const int32_t* src_word_map /*[B,S_src] dev*/, const int32_t* src_map_len /*[B] dev*/,
+                       const uint8_t* tgt_mask /*[B,S_tgt] dev*/, const int32_t* tgt_word_map /*[B,S_tgt] dev*/,
+                       const int32_t* tgt_map_len /*[B] dev*/, int64_t B, int32_t S_src, int32_t S_tgt,
+                       int32_t max_words, float ignore_value, float* out /*[B,S_tgt] dev*/,
+                       int64_t* out_bad_words /*[1] dev | NULL*/, void* stream);
+
+/* ------------------------------------------------------------------------
  * Diagnostic: sustained rate of the matrix cores on the MFMA instruction the
  * GEMM kernels use (bf16 16x16x32, fp32 accumulate), registers only, no memory
  * traffic.  random_operands = 0: constant operands (clock-limited peak);

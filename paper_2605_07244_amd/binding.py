@@ -95,6 +95,9 @@ def lib() -> ctypes.CDLL:
     L.mrl_profile_enable.argtypes = [c_int]
     L.mrl_profile_collect.restype = c_int
     L.mrl_profile_collect.argtypes = [POINTER(c_double), POINTER(c_int64)]
+    L.mrl_thl_word_align.restype = c_int
+    L.mrl_thl_word_align.argtypes = [c_void_p] * 7 + [c_int64, c_int32, c_int32, c_int32, c_float, c_void_p,
+                                                      c_void_p, c_void_p]
     L.mrl_probe_mfma_rate.restype = c_int
     L.mrl_probe_mfma_rate.argtypes = [c_int32, c_double, c_void_p, c_size_t, POINTER(c_double)]
     _LIB = L
@@ -250,3 +253,20 @@ def probe_mfma_rate(random_operands: bool, seconds: float = 0.5, device="cuda:0"
     _check(lib().mrl_probe_mfma_rate(1 if random_operands else 0, float(seconds), _ptr(scratch),
                                      scratch.numel(), ctypes.byref(out)), "mrl_probe_mfma_rate")
     return out.value
+
+
+def thl_word_align(src_logp, src_mask, src_word_map, src_map_len, tgt_mask, tgt_word_map, tgt_map_len,
+                   max_words: int, ignore_value: float = -100.0, want_bad_count: bool = True):
+    """Word-level trace alignment (App. D, Alg. 2).  Returns (out [B, S_tgt] float32, bad-entry count tensor)."""
+    B, S_src = src_logp.shape
+    S_tgt = tgt_mask.shape[1]
+    dev = src_logp.device
+    out = torch.empty((B, S_tgt), dtype=torch.float32, device=dev)
+    bad = torch.empty(1, dtype=torch.int64, device=dev) if want_bad_count else None
+    _check(lib().mrl_thl_word_align(
+        _ptr(src_logp, torch.float32, "src_logp"), _ptr(src_mask, torch.uint8, "src_mask"),
+        _ptr(src_word_map, torch.int32, "src_word_map"), _ptr(src_map_len, torch.int32, "src_map_len"),
+        _ptr(tgt_mask, torch.uint8, "tgt_mask"), _ptr(tgt_word_map, torch.int32, "tgt_word_map"),
+        _ptr(tgt_map_len, torch.int32, "tgt_map_len"), B, S_src, S_tgt, int(max_words), float(ignore_value),
+        _ptr(out), _ptr(bad) if bad is not None else None, _stream()), "mrl_thl_word_align")
+    return out, bad

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmrl.so")
-SOURCES = ["mrl_api.hip", "mrl_gemm_bf16.hip", "mrl_gemm_f32.hip", "mrl_aux.hip", "mrl_adv.hip", "mrl_probe.hip"]
+SOURCES = ["mrl_api.hip", "mrl_gemm_bf16.hip", "mrl_gemm_f32.hip", "mrl_aux.hip", "mrl_adv.hip", "mrl_probe.hip", "mrl_thl.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -69,6 +69,10 @@ int check_device() {
   return cache[dev] == 1 ? MRL_OK : MRL_ERR_UNSUPPORTED_ARCH;
 }
 
+}  // namespace
+int require_gfx950() { return check_device(); }
+namespace {
+
 // ------------------------------------------------------------------ workspace layout
 struct Layout {
   size_t total = 0;

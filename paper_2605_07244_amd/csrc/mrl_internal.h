@@ -133,6 +133,9 @@ void launch_finalize(const double* loss_partials, int64_t n_blocks, const int64_
                      const int64_t* n_bad, float beta, float lambda, int64_t rows_enqueued,
                      const int32_t* row_index, float* out_logp, void* out_stats, hipStream_t stream);
 
+// MRL_OK when the current device is a gfx950, else MRL_ERR_UNSUPPORTED_ARCH / MRL_ERR_DEVICE.
+int require_gfx950();
+
 // ---- profiling ---------------------------------------------------------------
 void prof_begin(int cls, hipStream_t stream);
 void prof_end(int cls, hipStream_t stream);

@@ -200,3 +200,55 @@ def seq_adv_from(adv_all: torch.Tensor, batch: dict) -> torch.Tensor:
     out = torch.zeros(batch["B"], dtype=torch.float32, device=adv_all.device)
     out[:batch["B_roll"]] = adv_all[:batch["B_roll"]]
     return out
+
+
+def make_thl(B: int, S_src: int, S_tgt: int, seed: int = SEED_BASE + 7, device="cuda",
+             p_none: float = 0.02, p_drop_word: float = 0.01, p_drift: float = 0.05,
+             prompt_max: int = 64) -> dict:
+    """Seeded inputs for the word-level trace alignment with the structure of retokenized peer
+    rollouts: a prompt prefix outside the response mask, then a response of whitespace words,
+    each split into 1-4 tokens independently on the source and on the target grid (target
+    1.0-1.3 x the source length on average, as in configuration 3), a few delimiter tokens
+    without a word, a few words missing on one side, and for a few sequences a map that is
+    shorter or longer than the response (incremental vs full tokenization drift).  Log-probs
+    are -Gamma(1, 1).  Built on the CPU with NumPy (integer bookkeeping), then moved to `device`.
+    """
+    import numpy as np
+    rng = np.random.default_rng(seed)
+    src_m = np.zeros((B, S_src), dtype=np.uint8)
+    tgt_m = np.zeros((B, S_tgt), dtype=np.uint8)
+    src_map = np.full((B, S_src), -1, dtype=np.int32)
+    tgt_map = np.full((B, S_tgt), -1, dtype=np.int32)
+    src_len = np.zeros(B, dtype=np.int32)
+    tgt_len = np.zeros(B, dtype=np.int32)
+    max_word = 0
+    for i in range(B):
+        pre_s, pre_t = (int(rng.integers(0, min(prompt_max, S // 4) + 1)) for S in (S_src, S_tgt))
+        budget = int(rng.integers(max(1, (S_src - pre_s) // 6), S_src - pre_s + 1))   # source response tokens
+        n_words = max(1, int(budget / 1.5))
+        split_s = rng.choice([1, 2, 3, 4], size=n_words, p=[0.62, 0.28, 0.08, 0.02])
+        ratio = rng.uniform(1.0, 1.3)
+        split_t = np.maximum(1, np.rint(split_s * ratio + rng.uniform(-0.5, 0.5, n_words))).astype(np.int64)
+        sides = []
+        for split, S, pre in ((split_s, S_src, pre_s), (split_t, S_tgt, pre_t)):
+            keep = rng.random(n_words) >= p_drop_word
+            words = np.repeat(np.arange(n_words)[keep], split[keep])
+            lead = int(rng.integers(0, 2))
+            words = np.concatenate([np.full(lead, -1, dtype=np.int64), words])
+            words = np.where(rng.random(words.size) < p_none, -1, words)[: S - pre]
+            n_resp = words.size
+            if rng.random() < p_drift and n_resp > 4:
+                n_resp = int(np.clip(n_resp + rng.integers(-3, 4), 0, S - pre))
+            sides.append((words, n_resp, pre))
+        (ws, ns, ps), (wt, nt, pt) = sides
+        src_m[i, ps:ps + ns] = 1
+        tgt_m[i, pt:pt + nt] = 1
+        src_map[i, :ws.size] = ws
+        tgt_map[i, :wt.size] = wt
+        src_len[i], tgt_len[i] = ws.size, wt.size
+        max_word = max(max_word, int(ws.max(initial=0)), int(wt.max(initial=0)))
+    src_lp = -rng.gamma(1.0, 1.0, size=(B, S_src)).astype(np.float32)
+    t = lambda a: torch.from_numpy(a).to(device)
+    return dict(src_logp=t(src_lp), src_mask=t(src_m), src_word_map=t(src_map), src_map_len=t(src_len),
+                tgt_mask=t(tgt_m), tgt_word_map=t(tgt_map), tgt_map_len=t(tgt_len),
+                max_words=max_word + 1, B=B, S_src=S_src, S_tgt=S_tgt)

@@ -143,3 +143,16 @@ def test_probe_argument_errors():
     assert f(0, 0.1, FAKE, 1 << 20, None) == -1
     assert f(0, 0.0, FAKE, 1 << 20, ctypes.byref(out)) == -7
     assert f(0, 60.0, FAKE, 1 << 20, ctypes.byref(out)) == -7
+
+
+def test_thl_word_align_argument_errors():
+    f = m.lib().mrl_thl_word_align
+    args = lambda **kw: [kw.get("p0", FAKE), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, kw.get("B", 4), kw.get("S", 16), 16,
+                         kw.get("W", 32), ctypes.c_float(-100.0), kw.get("out", FAKE), None, None]
+    assert f(*args(p0=None)) == -1
+    assert f(*args(out=None)) == -1
+    assert f(*args(S=0)) == -2
+    assert f(*args(B=-1)) == -2
+    assert f(*args(W=0)) == -2
+    assert f(*args(W=8193)) == -2
+    assert f(*args(B=0)) == 0          # empty batch: no-op
