@@ -85,6 +85,18 @@ def token_logprobs(H, W, target_ids, token_mask=None):
     return logp, lse
 
 
+def token_entropy(H, W, token_mask=None):
+    """Shannon entropy of the next-token distribution of every row, - sum_v p[n, v] log p[n, v]
+    (the per-token quantity behind the entropy traces of Sec. 5, "Optimization Diagnostics").
+    Masked rows report 0."""
+    logp_all, _ = log_softmax(logits(H, W))
+    p = np.exp(logp_all)
+    ent = -np.sum(np.where(p > 0.0, p * logp_all, 0.0), axis=1)
+    if token_mask is not None:
+        ent = np.where(np.asarray(token_mask).astype(bool), ent, 0.0)
+    return ent
+
+
 # --------------------------------------------------------------------------
 # Sec. 3 advantages; Sec. 5.1 pool-wide; App. G.1 pooled baseline; SGT gate
 # --------------------------------------------------------------------------

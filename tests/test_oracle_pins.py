@@ -518,3 +518,31 @@ def test_bf16_decode_exact():
     x = torch.randn(1000, dtype=torch.float32).to(torch.bfloat16)
     assert np.array_equal(orc.decode_bf16(x.view(torch.int16).numpy().view(np.uint16)),
                           x.to(torch.float64).numpy())
+
+
+# ---------------------------------------------------------------- token entropy
+def test_entropy_closed_forms_and_library():
+    import scipy.stats
+    rng = np.random.default_rng(11)
+    # uniform distribution: log V, whatever the common logit is
+    H = np.ones((3, 4))
+    W = np.tile(rng.normal(size=(1, 4)), (9, 1))
+    assert np.allclose(orc.token_entropy(H, W), np.log(9.0), atol=1e-12)
+    # two-point distribution with log-odds a: H = log(1 + e^a) - a * sigma(a)
+    a = 1.7
+    ent = orc.token_entropy(np.array([[1.0]]), np.array([[a], [0.0]]))[0]
+    assert abs(ent - (np.log1p(np.exp(a)) - a / (1.0 + np.exp(-a)))) < 1e-12
+    # library routine on random rows, and the identity H = lse - E_p[z]
+    H = rng.normal(size=(6, 5))
+    W = rng.normal(size=(13, 5))
+    z = orc.logits(H, W)
+    logp, lse = orc.log_softmax(z)
+    ent = orc.token_entropy(H, W)
+    assert np.allclose(ent, scipy.stats.entropy(np.exp(logp), axis=1), atol=1e-12)
+    assert np.allclose(ent, lse - np.sum(np.exp(logp) * z, axis=1), atol=1e-12)
+    # a sharply peaked row has entropy near 0, a masked row exactly 0
+    W2 = W.copy()
+    W2[4] *= 200.0
+    ent2 = orc.token_entropy(H, W2, token_mask=[1, 1, 1, 0, 1, 1])
+    assert ent2[3] == 0.0 and np.all(ent2 >= 0.0) and ent2.min() < 1e-6
+    assert np.all(ent <= np.log(13.0) + 1e-12)
