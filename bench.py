@@ -232,6 +232,21 @@ def main():
 
     thl_leg = thl_alignment_leg(mrl, synth, torch, with_cpu=not args.no_cpu_baseline)
 
+    # forward-only scoring pass (behaviour / reference traces, re-scoring of pooled peer rollouts):
+    # log-probs + entropy of the same batch, 2 N d V FLOP
+    ws_f = torch.empty(mrl.lib().mrl_token_scores_workspace(N, d, V, mrl.BF16), dtype=torch.uint8, device="cuda")
+    mrl.token_scores(batch["H"], batch["W"], batch["targets"], mask, workspace=ws_f)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(2):
+        mrl.token_scores(batch["H"], batch["W"], batch["targets"], mask, workspace=ws_f)
+    torch.cuda.synchronize()
+    dt_f = (time.perf_counter() - t0) / 2
+    del ws_f
+    fwd_leg = dict(outputs="logp, lse, entropy", ms_per_call=round(1e3 * dt_f, 2),
+                   tokens_per_s=round(n_scored / dt_f, 1),
+                   pct_bf16_mfma_peak=round(100.0 * 2.0 * n_scored * d * V / dt_f / (MFMA_BF16_PEAK_TFLOPS * 1e12), 2))
+
     base = None
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
@@ -245,7 +260,7 @@ def main():
                             rollouts_per_prompt=sp.k_own + sp.k_peer),
                 pct_bf16_mfma_peak=round(pct_peak, 2), flop_per_token=flop_per_token,
                 roofline=roofline, measured_mfma_peak=measured_peak, kernel_classes=classes,
-                hbm_passes=hbm_passes, thl_word_align=thl_leg, cpu_baseline=base,
+                hbm_passes=hbm_passes, thl_word_align=thl_leg, scoring_forward_only=fwd_leg, cpu_baseline=base,
                 loss=dict(total=stats["loss_total"], clip_frac=stats["n_clipped_tokens"] / max(n_scored, 1),
                           mean_ratio=stats["mean_ratio"]))
     print(json.dumps(line), flush=True)

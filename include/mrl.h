@@ -93,6 +93,24 @@ int mrl_token_logprobs(const void* hidden /*[N,d] dev*/, const void* lm_head_w /
                        float* out_logp /*[N] dev*/, float* out_lse /*[N] dev | NULL*/,
                        void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
+/* (1b) Scoring pass with diagnostics: the same log-probs plus, when out_entropy is not
+ *      NULL, the entropy of the next-token distribution of every scored row,
+ *        out_entropy[n] = - sum_v p[n, v] log p[n, v] = lse[n] - sum_v p[n, v] z[n, v],
+ *      the per-token quantity behind the entropy traces of Sec. 5 ("Optimization
+ *      Diagnostics").  This is the forward-only pass that produces the behaviour and
+ *      reference traces and re-scores pooled peer rollouts before the loss call.
+ *      Unscored rows report 0.  out_lse and out_entropy may be NULL; with out_entropy
+ *      NULL the call is mrl_token_logprobs.  The workspace query is its own because the
+ *      entropy needs a third partial per row and vocabulary tile. */
+size_t mrl_token_scores_workspace(int64_t N, int32_t d, int32_t V, int32_t dtype);
+int mrl_token_scores(const void* hidden /*[N,d] dev*/, const void* lm_head_w /*[V,d] dev*/,
+                     const int32_t* target_ids /*[N] dev*/,
+                     const uint8_t* token_mask /*[N] dev | NULL*/,
+                     int64_t N, int32_t d, int32_t V, int32_t dtype,
+                     float* out_logp /*[N] dev*/, float* out_lse /*[N] dev | NULL*/,
+                     float* out_entropy /*[N] dev | NULL*/,
+                     void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * (2) Group-relative advantages and the SGT gate.
  *     Sec. 3: rbar = mean of the group's rewards, A~ = r - rbar,

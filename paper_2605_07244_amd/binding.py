@@ -81,6 +81,11 @@ def lib() -> ctypes.CDLL:
     L.mrl_token_logprobs.restype = c_int
     L.mrl_token_logprobs.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32,
                                      c_int32, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mrl_token_scores_workspace.restype = c_size_t
+    L.mrl_token_scores_workspace.argtypes = [c_int64, c_int32, c_int32, c_int32]
+    L.mrl_token_scores.restype = c_int
+    L.mrl_token_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32,
+                                   c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     L.mrl_group_advantages.restype = c_int
     L.mrl_group_advantages.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                        c_int32, c_float, c_int32, c_float, c_float, c_float,
@@ -168,6 +173,27 @@ def token_logprobs(hidden, lm_head_w, target_ids, token_mask=None, workspace=Non
                                   _ptr(out_logp), _ptr(out_lse), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "mrl_token_logprobs")
     return out_logp, out_lse
+
+
+def token_scores(hidden, lm_head_w, target_ids, token_mask=None, workspace=None, want_lse=True,
+                 want_entropy=True):
+    """Forward-only scoring pass: (logp, lse | None, entropy | None), each [N] float32."""
+    N, d = hidden.shape
+    V = lm_head_w.shape[0]
+    dt = _dtype_code(hidden)
+    dev = hidden.device
+    need = lib().mrl_token_scores_workspace(N, d, V, dt) if want_entropy else \
+        lib().mrl_token_logprobs_workspace(N, d, V, dt)
+    if workspace is None:
+        workspace = _workspace(need, dev)
+    out_logp = torch.empty(N, dtype=torch.float32, device=dev)
+    out_lse = torch.empty(N, dtype=torch.float32, device=dev) if want_lse else None
+    out_ent = torch.empty(N, dtype=torch.float32, device=dev) if want_entropy else None
+    _check(lib().mrl_token_scores(_ptr(hidden), _ptr(lm_head_w), _ptr(target_ids, torch.int32, "target_ids"),
+                                  _ptr(token_mask, torch.uint8, "token_mask"), N, d, V, dt, _ptr(out_logp),
+                                  _ptr(out_lse), _ptr(out_ent), _ptr(workspace), workspace.numel(), _stream()),
+           "mrl_token_scores")
+    return out_logp, out_lse, out_ent
 
 
 def group_advantages(rewards, group_id, G, in_stats=None, scored=None, is_own=None, mode=ADV_GROUP_ZN,

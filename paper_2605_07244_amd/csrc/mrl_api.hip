@@ -76,7 +76,7 @@ namespace {
 // ------------------------------------------------------------------ workspace layout
 struct Layout {
   size_t total = 0;
-  size_t counters, row_index, block_counts, zt, part_max, part_sum;
+  size_t counters, row_index, block_counts, zt, part_max, part_sum, part_ez;
   size_t seq_len, seq_coef, group_count, lse_c, g_c, loss_partials, Z, Pt, Ht, Wt;
   int chunk_rows = 0, n_partials = 0;
   int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of Z/P and Wt, ldr: of Ht (and the fp32 path's Pt)
@@ -89,7 +89,8 @@ size_t take(size_t& off, size_t bytes) {
   return at;
 }
 
-Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows, bool loss) {
+Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows, bool loss,
+                   bool entropy = false) {
   Layout L;
   const bool bf16 = dtype == MRL_BF16;
   const size_t es = bf16 ? 2 : 4;
@@ -110,6 +111,7 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
   L.zt = take(off, (size_t)(N + 1) * 4);
   L.part_max = take(off, (size_t)L.n_partials * chunk_rows * 4);
   L.part_sum = take(off, (size_t)L.n_partials * chunk_rows * 4);
+  L.part_ez = entropy ? take(off, (size_t)L.n_partials * chunk_rows * 4) : 0;
   if (loss) {
     L.seq_len = take(off, (size_t)(B + 1) * 4);
     L.seq_coef = take(off, (size_t)(B + 1) * 4);
@@ -156,13 +158,13 @@ int check_cfg(const mrl_loss_config* c) {
 // pick the chunk size: the configured one, or the largest default-capped multiple of
 // 256 whose layout fits into the caller's workspace
 int pick_chunk(int64_t N, int64_t B, int d, int V, int dtype, int cfg_chunk, bool loss,
-               size_t workspace_bytes, Layout& L) {
+               size_t workspace_bytes, Layout& L, bool entropy = false) {
   if (cfg_chunk > 0) {
-    L = make_layout(N, B, d, V, dtype, cfg_chunk, loss);
+    L = make_layout(N, B, d, V, dtype, cfg_chunk, loss, entropy);
     return L.total <= workspace_bytes ? MRL_OK : MRL_ERR_WORKSPACE;
   }
   for (int r = default_chunk(N, dtype); r >= kTile; r = (r / 2) / kTile * kTile) {
-    L = make_layout(N, B, d, V, dtype, r, loss);
+    L = make_layout(N, B, d, V, dtype, r, loss, entropy);
     if (L.total <= workspace_bytes) return MRL_OK;
     if (r == kTile) break;
   }
@@ -179,7 +181,7 @@ int last_error() {
 
 // forward of one chunk: logits tile GEMM with fused (or, in fp32, separate) log-sum-exp
 void forward_chunk(const void* H, const void* W, int d, int V, bool bf16, const Layout& L, void* ws,
-                   int64_t c0, bool stash, hipStream_t s) {
+                   int64_t c0, bool stash, hipStream_t s, bool entropy = false) {
   const int32_t* row_index = at<int32_t>(ws, L.row_index);
   const int64_t* n_scored = at<int64_t>(ws, L.counters);
   if (bf16) {
@@ -187,7 +189,8 @@ void forward_chunk(const void* H, const void* W, int d, int V, bool bf16, const 
       const int rows = L.chunk_rows - sub < kFwdSubChunk ? L.chunk_rows - sub : kFwdSubChunk;
       Scope sc(MRL_PROF_GEMM_FWD, s);   // one event pair per kernel launch
       launch_gemm_fwd_bf16(W, H, row_index, n_scored, c0 + sub, rows, V, d, at<float>(ws, L.part_max) + sub,
-                           at<float>(ws, L.part_sum) + sub, L.chunk_rows,
+                           at<float>(ws, L.part_sum) + sub, entropy ? at<float>(ws, L.part_ez) + sub : nullptr,
+                           L.chunk_rows,
                            stash ? at<uint16_t>(ws, L.Z) + (size_t)sub * L.ldz : nullptr, L.ldz, s);
     }
   } else {
@@ -201,7 +204,7 @@ void forward_chunk(const void* H, const void* W, int d, int V, bool bf16, const 
     g.m_dynamic = 1; g.k_dynamic = 0; g.accumulate = 0;
     launch_gemm_f32(g, s);
     launch_row_lse_f32(at<float>(ws, L.Z), L.ldz, n_scored, c0, L.chunk_rows, V, at<float>(ws, L.part_max),
-                       at<float>(ws, L.part_sum), s);
+                       at<float>(ws, L.part_sum), entropy ? at<float>(ws, L.part_ez) : nullptr, s);
   }
 }
 
@@ -263,17 +266,23 @@ size_t mrl_token_logprobs_workspace(int64_t N, int32_t d, int32_t V, int32_t dty
   return make_layout(N, 0, d, V, dtype, default_chunk(N, dtype), false).total;
 }
 
-int mrl_token_logprobs(const void* hidden, const void* lm_head_w, const int32_t* target_ids,
-                       const uint8_t* token_mask, int64_t N, int32_t d, int32_t V, int32_t dtype,
-                       float* out_logp, float* out_lse, void* workspace, size_t workspace_bytes,
-                       void* stream) {
+size_t mrl_token_scores_workspace(int64_t N, int32_t d, int32_t V, int32_t dtype) {
+  if (check_common(N, d, V, dtype) != MRL_OK) return 0;
+  return make_layout(N, 0, d, V, dtype, default_chunk(N, dtype), false, true).total;
+}
+
+int mrl_token_scores(const void* hidden, const void* lm_head_w, const int32_t* target_ids,
+                     const uint8_t* token_mask, int64_t N, int32_t d, int32_t V, int32_t dtype,
+                     float* out_logp, float* out_lse, float* out_entropy, void* workspace,
+                     size_t workspace_bytes, void* stream) {
   if (!hidden || !lm_head_w || !target_ids || !out_logp) return MRL_ERR_NULL;
   int rc = check_common(N, d, V, dtype);
   if (rc != MRL_OK) return rc;
   if (N == 0) return MRL_OK;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return MRL_ERR_WORKSPACE;
+  const bool entropy = out_entropy != nullptr;
   Layout L;
-  rc = pick_chunk(N, 0, d, V, dtype, 0, false, workspace_bytes, L);
+  rc = pick_chunk(N, 0, d, V, dtype, 0, false, workspace_bytes, L, entropy);
   if (rc != MRL_OK) return rc;
   rc = check_device();
   if (rc != MRL_OK) return rc;
@@ -288,20 +297,30 @@ int mrl_token_logprobs(const void* hidden, const void* lm_head_w, const int32_t*
     PrepOut po = {row_index, n_scored, n_scored + 1, at<int32_t>(ws, L.block_counts)};
     launch_prep(token_mask, target_ids, N, V, po, s);
     launch_zero_unscored(token_mask, target_ids, N, V, d, out_logp, out_lse, nullptr, 0, s);
+    if (entropy) launch_zero_unscored(token_mask, target_ids, N, V, d, out_entropy, nullptr, nullptr, 0, s);
     launch_target_logit(hidden, lm_head_w, target_ids, row_index, n_scored, N, d, bf16, at<float>(ws, L.zt), s);
   }
   for (int64_t c = 0; c < L.n_chunks; ++c) {
     const int64_t c0 = c * L.chunk_rows;
-    forward_chunk(hidden, lm_head_w, d, V, bf16, L, ws, c0, false, s);
+    forward_chunk(hidden, lm_head_w, d, V, bf16, L, ws, c0, false, s, entropy);
     Scope sc(MRL_PROF_ROW_EPI, s);
     RowEpiArgs e = {};
     e.part_max = at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
+    e.part_ez = entropy ? at<float>(ws, L.part_ez) : nullptr; e.out_entropy = out_entropy;
     e.n_partials = L.n_partials; e.chunk_rows = L.chunk_rows;
     e.zt = at<float>(ws, L.zt); e.row_index = row_index; e.n_scored = n_scored; e.chunk_start = c0;
     e.out_logp = out_logp; e.out_lse = out_lse;
     launch_row_epilogue(e, s);
   }
   return last_error();
+}
+
+int mrl_token_logprobs(const void* hidden, const void* lm_head_w, const int32_t* target_ids,
+                       const uint8_t* token_mask, int64_t N, int32_t d, int32_t V, int32_t dtype,
+                       float* out_logp, float* out_lse, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  return mrl_token_scores(hidden, lm_head_w, target_ids, token_mask, N, d, V, dtype, out_logp, out_lse,
+                          nullptr, workspace, workspace_bytes, stream);
 }
 
 // --------------------------------------------------------------------------- (2)

@@ -275,7 +275,7 @@ __global__ __launch_bounds__(256) void k_target_logit(const void* H, const void*
 // ----------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_row_lse_f32(const float* Z, int64_t ldz, const int64_t* n_scored,
                                                      int64_t chunk_start, int chunk_rows, int V,
-                                                     float* part_max, float* part_sum) {
+                                                     float* part_max, float* part_sum, float* part_ez) {
   const int i = blockIdx.x;
   if (i >= valid_rows(n_scored, chunk_start, chunk_rows)) return;
   __shared__ float sh[256];
@@ -299,6 +299,17 @@ __global__ __launch_bounds__(256) void k_row_lse_f32(const float* Z, int64_t ldz
     __syncthreads();
   }
   if (threadIdx.x == 0) { part_max[i] = mx; part_sum[i] = sh[0]; }
+  if (part_ez == nullptr) return;
+  __syncthreads();
+  float t = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) t += expf(z[v] - mx) * z[v];
+  sh[threadIdx.x] = t;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) part_ez[i] = sh[0];
 }
 
 // ----------------------------------------------------------------------------
@@ -325,15 +336,27 @@ __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
   sh_m[ty][tx] = mx;
   __syncthreads();
   mx = fmaxf(fmaxf(sh_m[0][tx], sh_m[1][tx]), fmaxf(sh_m[2][tx], sh_m[3][tx]));
-  float s = 0.f;
+  float s = 0.f, t = 0.f;
   if (live)
     for (int p = ty; p < a.n_partials; p += 4) {
       const float pm = a.part_max[(int64_t)p * a.chunk_rows + i];
       const float ps = a.part_sum[(int64_t)p * a.chunk_rows + i];
-      s += pm == -INFINITY ? 0.f : ps * expf(pm - mx);
+      const float sc = pm == -INFINITY ? 0.f : expf(pm - mx);
+      s += ps * sc;
+      if (a.part_ez != nullptr) t += a.part_ez[(int64_t)p * a.chunk_rows + i] * sc;
     }
   sh_s[ty][tx] = s;
   __syncthreads();
+  if (a.part_ez != nullptr) {
+    // entropy H = lse - (sum_v exp(z - max) z) / (sum_v exp(z - max)); sh_m is free again
+    sh_m[ty][tx] = t;
+    __syncthreads();
+    if (ty == 0 && live) {
+      const float ssum = (sh_s[0][tx] + sh_s[1][tx]) + (sh_s[2][tx] + sh_s[3][tx]);
+      const float tsum = (sh_m[0][tx] + sh_m[1][tx]) + (sh_m[2][tx] + sh_m[3][tx]);
+      a.out_entropy[a.row_index[a.chunk_start + i]] = (mx + logf(ssum)) - tsum / ssum;
+    }
+  }
 
   double q[EPI_NQ];
 #pragma unroll
@@ -643,9 +666,10 @@ void launch_target_logit(const void* H, const void* W, const int32_t* targets,
 }
 
 void launch_row_lse_f32(const float* Z, int64_t ldz, const int64_t* n_scored, int64_t chunk_start,
-                        int chunk_rows, int V, float* part_max, float* part_sum, hipStream_t stream) {
+                        int chunk_rows, int V, float* part_max, float* part_sum, float* part_ez,
+                        hipStream_t stream) {
   hipLaunchKernelGGL(k_row_lse_f32, dim3(chunk_rows), dim3(256), 0, stream, Z, ldz, n_scored, chunk_start,
-                     chunk_rows, V, part_max, part_sum);
+                     chunk_rows, V, part_max, part_sum, part_ez);
 }
 
 int row_epilogue_blocks(int chunk_rows) { return (chunk_rows + EPI_ROWS - 1) / EPI_ROWS; }

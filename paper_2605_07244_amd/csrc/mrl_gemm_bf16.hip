@@ -89,7 +89,7 @@ struct Params {
   const int32_t* row_index;   // already offset to the chunk start
   const int64_t* n_scored; int64_t chunk_start; int chunk_rows;
   // FWD
-  float* part_max; float* part_sum; int64_t part_stride; uint16_t* zstash; int64_t ldz; int V;
+  float* part_max; float* part_sum; float* part_ez; int64_t part_stride; uint16_t* zstash; int64_t ldz; int V;
   // DH
   void* dH; int dh_f32; int d;
   // DW
@@ -454,6 +454,21 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         p.part_max[(int64_t)pidx * p.part_stride + n] = mx;
         p.part_sum[(int64_t)pidx * p.part_stride + n] = s;
       }
+      if (p.part_ez != nullptr) {
+        // third partial for the entropy: sum_v exp(z - max) * z  (H = lse - E_p[z])
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float z = acc[i][j][e];
+            const float w = exp2_fast(fmaf(z, LOG2E, mneg));
+            t += (full || (mrow_base + i * 16 + e) < p.V) ? w * z : 0.f;
+          }
+        t += __shfl_xor(t, 16);
+        t += __shfl_xor(t, 32);
+        if (fq == 0 && n < N) p.part_ez[(int64_t)pidx * p.part_stride + n] = t;
+      }
       if (p.zstash != nullptr) {
         // stage the logits as fp16 in LDS, [token][vocab], for coalesced row stores below
         unsigned char* srow = smem + (wn * 128 + j * 16 + frow) * (STASH_LD * 2) + (wm * 128 + 4 * fq) * 2;
@@ -569,15 +584,15 @@ void launch(const Params& p, hipStream_t stream) {
 
 void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                          int V, int d, float* part_max, float* part_sum, int64_t part_stride,
-                          void* zstash, int64_t ldz, hipStream_t stream) {
+                          int V, int d, float* part_max, float* part_sum, float* part_ez,
+                          int64_t part_stride, void* zstash, int64_t ldz, hipStream_t stream) {
   Params p = {};
   p.A = static_cast<const uint16_t*>(W); p.lda = d; p.M = V;
   p.B = static_cast<const uint16_t*>(H); p.ldb = d; p.N = chunk_rows;
   p.K = d;
   p.row_index = row_index + chunk_start;
   p.n_scored = n_scored; p.chunk_start = chunk_start; p.chunk_rows = chunk_rows;
-  p.part_max = part_max; p.part_sum = part_sum; p.part_stride = part_stride;
+  p.part_max = part_max; p.part_sum = part_sum; p.part_ez = part_ez; p.part_stride = part_stride;
   p.zstash = static_cast<uint16_t*>(zstash); p.ldz = ldz; p.V = V; p.d = d;
   launch<MODE_FWD>(p, stream);
 }

@@ -22,11 +22,13 @@ inline int fwd_partials_bf16(int V) { return 2 * (int)((V + kTile - 1) / kTile);
 
 // Forward: A = W [V, d], B = H rows gathered through row_index[chunk_start + n].
 // Writes per-row partials part_max/part_sum[(2*tile_m + wave_m) * part_stride + n]
-// and, when zstash != nullptr, the logits as fp16 into zstash[n * ldz + v] (n = row within this launch).
+// (max and sum exp(z - max) over the partial's 128 vocabulary rows), when part_ez != nullptr also
+// sum exp(z - max) * z (for the entropy), and, when zstash != nullptr, the logits as fp16 into
+// zstash[n * ldz + v] (n = row within this launch).
 void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                          int V, int d, float* part_max, float* part_sum, int64_t part_stride,
-                          void* zstash, int64_t ldz, hipStream_t stream);
+                          int V, int d, float* part_max, float* part_sum, float* part_ez,
+                          int64_t part_stride, void* zstash, int64_t ldz, hipStream_t stream);
 
 // dH: A = P [chunk_rows, Vp] (bf16 dz), B = Wt [d, Vp]; row m goes to
 // dH[row_index[chunk_start + m], :] as bf16 (dh_f32 = 0) or float (dh_f32 = 1).
@@ -84,12 +86,14 @@ void launch_target_logit(const void* H, const void* W, const int32_t* targets,
                          const int32_t* row_index, const int64_t* n_scored, int64_t N_max,
                          int d, int is_bf16, float* zt, hipStream_t stream);
 
-// fp32 path: (max, sum-exp) of each row of Z [rows, V] -> one partial per row.
+// fp32 path: (max, sum-exp[, sum exp * z]) of each row of Z [rows, V] -> one partial per row.
 void launch_row_lse_f32(const float* Z, int64_t ldz, const int64_t* n_scored, int64_t chunk_start,
-                        int chunk_rows, int V, float* part_max, float* part_sum, hipStream_t stream);
+                        int chunk_rows, int V, float* part_max, float* part_sum, float* part_ez,
+                        hipStream_t stream);
 
 struct RowEpiArgs {
   const float* part_max; const float* part_sum; int n_partials; int chunk_rows;
+  const float* part_ez; float* out_entropy;   // both nullptr unless the entropy is asked for (per slot)
   const float* zt;            // [N] compacted
   const int32_t* row_index; const int64_t* n_scored; int64_t chunk_start;
   // loss inputs (all nullptr for the log-prob-only entry point)

@@ -156,3 +156,14 @@ def test_thl_word_align_argument_errors():
     assert f(*args(W=0)) == -2
     assert f(*args(W=8193)) == -2
     assert f(*args(B=0)) == 0          # empty batch: no-op
+
+
+def test_token_scores_argument_errors():
+    lib = m.lib()
+    f = lib.mrl_token_scores
+    assert f(None, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, None, FAKE, 1 << 20, None) == -1
+    assert f(FAKE, FAKE, FAKE, None, 8, 72, 32, 1, FAKE, None, FAKE, FAKE, 1 << 20, None) == -2
+    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, FAKE, FAKE, 16, None) == -6    # workspace too small
+    assert f(FAKE, FAKE, FAKE, None, 0, 64, 32, 1, FAKE, None, FAKE, None, 0, None) == 0
+    # the entropy needs a third partial buffer: its workspace is the larger one
+    assert lib.mrl_token_scores_workspace(4096, 256, 4000, 1) > lib.mrl_token_logprobs_workspace(4096, 256, 4000, 1)

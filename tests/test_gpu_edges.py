@@ -234,3 +234,31 @@ def test_mfma_rate_probe(mrl):
     assert 300.0 < const < 2600.0, const
     assert 300.0 < rnd < 2600.0, rnd
     assert rnd < 1.05 * const
+
+
+@pytest.mark.parametrize("dtype,scale", [(torch.bfloat16, 1.0), (torch.bfloat16, 8.0), (torch.float32, 1.0)])
+def test_token_scores_entropy(mrl, synth, dtype, scale):
+    """Forward-only scoring pass with the entropy output against the oracle: several vocabulary
+    tiles with a ragged last one, masked rows, and a peaked softmax (hidden states scaled by 8)."""
+    sp = synth.spec(2, n_prompts=2, T=40, V=2700, d=192, dtype=dtype)
+    b = synth.make(sp, "cuda")
+    Hs = (b["H"].float() * scale).to(dtype)
+    H, W, y = util.to_f64(Hs), util.to_f64(b["W"]), b["targets"].cpu().numpy()
+    mask = b["mask"].reshape(-1)
+    m = mask.cpu().numpy().astype(bool)
+    want_lp, want_lse = orc.token_logprobs(H, W, y, m)
+    want_ent = orc.token_entropy(H, W, m)
+    tol = util.LOGP_TOL if dtype == torch.bfloat16 else util.F32_LOGP_TOL
+    lp, lse, ent = mrl.token_scores(Hs, b["W"], b["targets"], mask)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(lp.cpu().numpy() - want_lp)) <= tol
+    assert np.max(np.abs(lse.cpu().numpy() - want_lse)) <= tol
+    assert np.max(np.abs(ent.cpu().numpy() - want_ent)) <= tol
+    assert torch.all(ent[~mask.bool()] == 0)
+    assert float(ent.max()) <= np.log(sp.V) + 1e-3 and float(ent.min()) >= -1e-3
+    # the log-probs are those of the plain entry point, bit for bit
+    lp0, lse0 = mrl.token_logprobs(Hs, b["W"], b["targets"], mask)
+    lp1, none_lse, none_ent = mrl.token_scores(Hs, b["W"], b["targets"], mask, want_lse=False, want_entropy=False)
+    torch.cuda.synchronize()
+    assert torch.equal(lp0, lp) and torch.equal(lse0, lse) and torch.equal(lp1, lp)
+    assert none_lse is None and none_ent is None
