@@ -268,6 +268,12 @@ def loss_from_logp(logp, token_mask, behav_logp, ref_logp, seq_adv, group_id, se
     Statistics: a token is "clipped" when its ratio lies outside
     [1 - eps_lo, 1 + eps_hi] (App. F, token-ratio table caption); it has zero
     surrogate gradient when s2 < s1.  Means run over scored GRPO tokens.
+
+    cfg["ratio_level"] (default 0 = the token ratio of Eq. 1) selects the response-level ratio
+    of App. G.1 instead: 1 = exp of the summed log-ratio, 2 = exp of its per-token mean (the
+    magnitudes of App. F's sequence-ratio table, medians 0.75-0.91 over whole responses, are
+    those of a per-token mean).  The KL term stays per token.  Statistics then use the
+    response's ratio for each of its tokens.
     """
     N = B * T
     m = np.asarray(token_mask).astype(bool).reshape(B, T)
@@ -282,6 +288,25 @@ def loss_from_logp(logp, token_mask, behav_logp, ref_logp, seq_adv, group_id, se
         np.where(mflat, np.asarray(ref_logp, dtype=np.float64).reshape(N), 0.0)
     w, s1, s2, J, dJ, k3, dk3 = token_terms(l, beh, ref, adv_tok,
                                             cfg["clip_eps_low"], cfg["clip_eps_high"])
+    level = int(cfg.get("ratio_level", 0))
+    if level != 0:
+        # Response-level ratio of App. G.1: rho_b = exp{L_theta - L_behavior} with the sums over the
+        # response's scored tokens (level 1), or their per-token mean (level 2); it takes the place
+        # of the token ratio in Eq. (1).  Every token of a response then carries the response's J,
+        # so E_tok[J] = J_b, and d rho_b / d l_t = rho_b (level 1) or rho_b / L_b (level 2).
+        if cfg.get("loss_agg", 0) != 0:
+            raise ValueError("the response-level ratio is defined for the Eq. (1) aggregation only")
+        L_b = m.sum(axis=1).astype(np.float64)
+        delta = np.where(mflat, l - beh, 0.0).reshape(B, T).sum(axis=1)
+        expo = delta if level == 1 else np.where(L_b > 0, delta / np.maximum(L_b, 1.0), 0.0)
+        rho_tok = np.repeat(np.exp(expo), T)
+        A = adv_tok
+        w = rho_tok
+        s1 = w * A
+        s2 = np.minimum(np.maximum(w, 1.0 - cfg["clip_eps_low"]), 1.0 + cfg["clip_eps_high"]) * A
+        J = np.minimum(s1, s2)
+        scale = np.repeat(L_b, T) if level == 1 else 1.0
+        dJ = np.where(s1 <= s2, w * A, 0.0) * scale
     beta, lam = float(cfg["kl_beta"]), float(cfg["sgt_lambda"])
     loss_pg = -float(np.sum(c * J))
     loss_kl = float(np.sum(c * k3))

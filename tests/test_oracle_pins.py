@@ -546,3 +546,93 @@ def test_entropy_closed_forms_and_library():
     ent2 = orc.token_entropy(H, W2, token_mask=[1, 1, 1, 0, 1, 1])
     assert ent2[3] == 0.0 and np.all(ent2 >= 0.0) and ent2.min() < 1e-6
     assert np.all(ent <= np.log(13.0) + 1e-12)
+
+
+# ---------------------------------------------------------------- response-level ratio (App. G.1)
+def _seq_tiny(seed, jitter=0.12):
+    """Like _tiny, with jitters such that response-level ratios straddle the clip band."""
+    t = _tiny(seed, B=6, T=4, G=3, V=9, d=4)
+    rng = np.random.default_rng(seed + 1000)
+    t["behav"] = t["logp"] - rng.normal(size=t["logp"].shape) * jitter
+    return t
+
+
+@pytest.mark.parametrize("level", [1, 2])
+def test_response_ratio_by_hand_and_autograd(level):
+    t = _seq_tiny(50, 0.12 if level == 1 else 0.4)
+    cfg = dict(CFG, ratio_level=level)
+    kind = np.array([0, 0, 0, 0, 0, 1])
+    res = _run(t, cfg=cfg, seq_kind=kind)
+    B, T = t["B"], t["T"]
+    m = t["m"]
+    # literal nested loops: rho_b from the response's summed log-ratio, J_b once per response
+    lp = res["logp"].reshape(B, T)
+    beh = t["behav"].reshape(B, T)
+    K = np.zeros(t["G"])
+    for b in range(B):
+        if kind[b] == 0:
+            K[t["gid"][b]] += 1
+    P = np.sum(K > 0)
+    total, ratios = 0.0, []
+    for b in range(B):
+        L = m[b].sum()
+        if kind[b] != 0 or L == 0:
+            continue
+        delta = sum(lp[b, j] - beh[b, j] for j in range(T) if m[b, j])
+        rho = np.exp(delta if level == 1 else delta / L)
+        ratios.append(rho)
+        A = t["adv"][b]
+        total += -min(rho * A, min(max(rho, 0.8), 1.2) * A) / (P * K[t["gid"][b]])
+    assert abs(res["loss_pg"] - total) < 1e-13
+    assert min(ratios) < 0.8 or max(ratios) > 1.2          # the clip is exercised
+    # independent backward
+    H = torch.tensor(t["H"], dtype=torch.float64, requires_grad=True)
+    W = torch.tensor(t["W"], dtype=torch.float64, requires_grad=True)
+    lpt = torch.log_softmax(H @ W.T, dim=1).gather(1, torch.tensor(t["y"])[:, None])[:, 0].reshape(B, T)
+    mt = torch.tensor(m)
+    d = torch.where(mt, lpt - torch.tensor(beh), torch.zeros_like(lpt)).sum(dim=1)
+    Lb = mt.sum(dim=1).clamp(min=1).double()
+    rho = torch.exp(d if level == 1 else d / Lb)
+    A = torch.tensor(t["adv"])
+    J = torch.minimum(rho * A, torch.clamp(rho, 0.8, 1.2) * A)
+    wseq = torch.tensor([(1.0 / (P * K[t["gid"][b]])) if (kind[b] == 0 and m[b].sum() > 0) else 0.0 for b in range(B)])
+    c = torch.tensor(res["c"]).reshape(B, T)
+    cs = torch.tensor(res["c_sgt"]).reshape(B, T)
+    r = torch.tensor(t["ref"]).reshape(B, T) - lpt
+    loss = -(wseq * J).sum() + CFG["kl_beta"] * (c * (torch.exp(r) - r - 1)).sum() - CFG["sgt_lambda"] * (cs * lpt).sum()
+    loss.backward()
+    assert abs(loss.item() - res["loss_total"]) < 1e-13
+    assert np.allclose(H.grad.numpy(), res["dH"], atol=1e-13)
+    assert np.allclose(W.grad.numpy(), res["dW"], atol=1e-13)
+
+
+def test_response_ratio_special_cases():
+    t = _seq_tiny(51)
+    base = _run(t)
+    # one-token responses: the response ratio is the token ratio, all three levels coincide
+    one = dict(t)
+    one["m"] = np.zeros_like(t["m"])
+    one["m"][:, 0] = True
+    r0 = _run(one)
+    for level in (1, 2):
+        r = _run(one, cfg=dict(CFG, ratio_level=level))
+        assert abs(r["loss_total"] - r0["loss_total"]) < 1e-15
+        assert np.allclose(r["dW"], r0["dW"], atol=1e-15)
+    # behaviour trace = current trace: rho = 1, J = A, clip inactive, gradient -A / (P K) per token
+    # at level 1 and -A / (P K L) at level 2
+    for level in (1, 2):
+        r = _run(t, cfg=dict(CFG, ratio_level=level, kl_beta=0.0), behav=base["logp"])
+        m = t["m"]
+        Kg = np.bincount(t["gid"], minlength=t["G"])
+        wseq = 1.0 / (t["G"] * Kg[t["gid"]])
+        assert abs(r["loss_pg"] + np.sum(wseq * t["adv"] * (m.sum(axis=1) > 0))) < 1e-14
+        assert r["n_clipped_tokens"] == 0
+        expect = -(wseq * t["adv"])[:, None] * m / (1.0 if level == 1 else np.maximum(m.sum(axis=1), 1)[:, None])
+        assert np.allclose(r["g"].reshape(m.shape), expect, atol=1e-15)
+    # the clipped weight never exceeds 1 + eps in magnitude (App. G, proof of the PRP theorem)
+    r = _run(t, cfg=dict(CFG, ratio_level=1))
+    A = np.repeat(t["adv"], t["T"])
+    live = t["m"].reshape(-1) & (np.abs(A) > 0)
+    assert np.all(np.abs(r["s2"][live] / A[live]) <= 1.2 + 1e-15)
+    with pytest.raises(ValueError):
+        _run(t, cfg=dict(CFG, ratio_level=1, loss_agg=1))
