@@ -181,6 +181,17 @@ typedef struct {
                                ceil(B*T / chunk_rows).  If the mask holds more scored slots than the
                                hint, the excess rows are NOT processed: their out_logp is NaN and
                                n_unprocessed_rows reports how many.                              */
+  int32_t ratio_level;   /* which importance ratio enters Eq. (1):
+                            0 = per token, w_t = exp(l_t - l_beh,t)                (Sec. 3)
+                            1 = per response, exp{L_theta - L_behavior}, L = sums over the
+                                response's scored tokens                           (App. G.1)
+                            2 = per response, exp of the per-token mean of the same sum (the
+                                magnitudes of App. F's sequence-ratio table are those of a mean)
+                            Levels 1 and 2 need loss_agg = 0; the KL term stays per token; the
+                            ratio statistics then count each token with its response's ratio.
+                            They run the forward contraction twice (the response sums must be
+                            complete before any token's gradient weight is known).           */
+  int32_t reserved;      /* must be 0 */
 } mrl_loss_config;
 
 typedef struct {

@@ -35,7 +35,8 @@ def library_path() -> str:
 class _LossConfig(ctypes.Structure):
     _fields_ = [("clip_eps_low", c_float), ("clip_eps_high", c_float), ("kl_beta", c_float),
                 ("sgt_lambda", c_float), ("loss_agg", c_int32), ("accumulate_dw", c_int32),
-                ("dh_dtype", c_int32), ("chunk_rows", c_int32), ("scored_rows_hint", c_int64)]
+                ("dh_dtype", c_int32), ("chunk_rows", c_int32), ("scored_rows_hint", c_int64),
+                ("ratio_level", c_int32), ("reserved", c_int32)]
 
 
 @dataclass
@@ -49,11 +50,12 @@ class LossConfig:
     dh_dtype: int = BF16
     chunk_rows: int = 0
     scored_rows_hint: int = 0
+    ratio_level: int = 0
 
     def to_c(self) -> _LossConfig:
         return _LossConfig(self.clip_eps_low, self.clip_eps_high, self.kl_beta, self.sgt_lambda,
                            self.loss_agg, self.accumulate_dw, self.dh_dtype, self.chunk_rows,
-                           self.scored_rows_hint)
+                           self.scored_rows_hint, self.ratio_level, 0)
 
 
 STATS_FIELDS = ("loss_total", "loss_pg", "loss_kl", "loss_sgt", "mean_ratio", "max_ratio", "mean_k3",

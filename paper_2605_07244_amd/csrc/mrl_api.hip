@@ -77,7 +77,7 @@ namespace {
 struct Layout {
   size_t total = 0;
   size_t counters, row_index, block_counts, zt, part_max, part_sum, part_ez;
-  size_t seq_len, seq_coef, group_count, lse_c, g_c, loss_partials, Z, Pt, Ht, Wt;
+  size_t seq_len, seq_coef, seq_expo, group_count, lse_c, g_c, loss_partials, Z, Pt, Ht, Wt;
   int chunk_rows = 0, n_partials = 0;
   int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of Z/P and Wt, ldr: of Ht (and the fp32 path's Pt)
   int64_t epi_blocks_total = 0;
@@ -115,6 +115,7 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
   if (loss) {
     L.seq_len = take(off, (size_t)(B + 1) * 4);
     L.seq_coef = take(off, (size_t)(B + 1) * 4);
+    L.seq_expo = take(off, (size_t)(B + 1) * 4);
     L.group_count = take(off, (size_t)(B + 1) * 4);
     L.lse_c = take(off, (size_t)(N + 1) * 4);
     L.g_c = take(off, (size_t)(N + 1) * 4);
@@ -152,6 +153,8 @@ int check_cfg(const mrl_loss_config* c) {
   if (c->dh_dtype != MRL_F32 && c->dh_dtype != MRL_BF16) return MRL_ERR_CONFIG;
   if (c->chunk_rows < 0 || c->chunk_rows % kTile != 0 || c->chunk_rows > (1 << 20)) return MRL_ERR_CONFIG;
   if (c->scored_rows_hint < 0) return MRL_ERR_CONFIG;
+  if (c->ratio_level < 0 || c->ratio_level > 2 || c->reserved != 0) return MRL_ERR_CONFIG;
+  if (c->ratio_level != 0 && c->loss_agg != 0) return MRL_ERR_CONFIG;
   return MRL_OK;
 }
 
@@ -413,6 +416,25 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     const int64_t by_hint = (cfg->scored_rows_hint + L.chunk_rows - 1) / L.chunk_rows;
     n_passes = by_hint < n_passes ? by_hint : n_passes;
   }
+  if (cfg->ratio_level != 0) {
+    // Response-level ratio: a response may span several passes, so the log-probs of all rows are
+    // computed first (forward only, no stash), then summed per response; the main loop below
+    // recomputes them (same bits) on its way to the gradients.
+    for (int64_t c = 0; c < n_passes; ++c) {
+      const int64_t c0 = c * L.chunk_rows;
+      forward_chunk(hidden, lm_head_w, d, V, bf16, L, ws, c0, false, s);
+      Scope sc(MRL_PROF_ROW_EPI, s);
+      RowEpiArgs e = {};
+      e.part_max = at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
+      e.n_partials = L.n_partials; e.chunk_rows = L.chunk_rows;
+      e.zt = at<float>(ws, L.zt); e.row_index = row_index; e.n_scored = n_scored; e.chunk_start = c0;
+      e.out_logp = out_logp;
+      launch_row_epilogue(e, s);
+    }
+    Scope sc(MRL_PROF_ROW_EPI, s);
+    launch_seq_log_ratio(token_mask, target_ids, out_logp, behav_logp, B, T, V, cfg->ratio_level,
+                         at<float>(ws, L.seq_expo), s);
+  }
   for (int64_t c = 0; c < n_passes; ++c) {
     const int64_t c0 = c * L.chunk_rows;
     forward_chunk(hidden, lm_head_w, d, V, bf16, L, ws, c0, bwd, s);
@@ -424,6 +446,8 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
       e.zt = at<float>(ws, L.zt); e.row_index = row_index; e.n_scored = n_scored; e.chunk_start = c0;
       e.behav_logp = behav_logp; e.ref_logp = beta > 0.f ? ref_logp : nullptr; e.seq_adv = seq_adv;
       e.seq_coef = at<float>(ws, L.seq_coef); e.seq_kind = seq_kind; e.T = T;
+      e.seq_expo = cfg->ratio_level != 0 ? at<float>(ws, L.seq_expo) : nullptr;
+      e.seq_len = at<int32_t>(ws, L.seq_len); e.ratio_level = cfg->ratio_level;
       e.eps_lo = cfg->clip_eps_low; e.eps_hi = cfg->clip_eps_high; e.beta = beta; e.lambda = cfg->sgt_lambda;
       e.out_logp = out_logp; e.out_lse = nullptr;
       e.lse_c = at<float>(ws, L.lse_c); e.g_c = at<float>(ws, L.g_c);

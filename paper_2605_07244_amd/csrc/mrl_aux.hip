@@ -205,6 +205,31 @@ __global__ __launch_bounds__(1024) void k_seq_coef(const int32_t* seq_len, const
 }
 
 // ----------------------------------------------------------------------------
+// Response-level log-ratio: one workgroup per sequence, fp64 partial sums, fixed order.
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_seq_log_ratio(const uint8_t* mask, const int32_t* targets,
+                                                       const float* logp, const float* behav, int T, int V,
+                                                       int level, float* seq_expo) {
+  __shared__ double sh[256];
+  __shared__ int shn[256];
+  const int64_t b = blockIdx.x;
+  double acc = 0.0;
+  int cnt = 0;
+  for (int t = threadIdx.x; t < T; t += 256) {
+    const int64_t n = b * T + t;
+    if (slot_valid(mask, targets, n, V)) { acc += (double)logp[n] - (double)behav[n]; ++cnt; }
+  }
+  sh[threadIdx.x] = acc;
+  shn[threadIdx.x] = cnt;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (threadIdx.x < off) { sh[threadIdx.x] += sh[threadIdx.x + off]; shn[threadIdx.x] += shn[threadIdx.x + off]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) seq_expo[b] = (float)(level == 2 ? (shn[0] > 0 ? sh[0] / shn[0] : 0.0) : sh[0]);
+}
+
+// ----------------------------------------------------------------------------
 // Zero the outputs of unscored slots.
 // ----------------------------------------------------------------------------
 constexpr int ZERO_SLOTS_PER_BLOCK = 16;
@@ -377,12 +402,15 @@ __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
       float g;
       if (kind == 0) {
         const float A = a.seq_adv[b];
-        const float w = expf(logp - a.behav_logp[slot]);
+        // token ratio of Eq. (1), or the response's ratio (App. G.1) whose derivative with
+        // respect to each token's log-prob is rho (summed form) or rho / L_b (mean form)
+        const float w = a.seq_expo ? expf(a.seq_expo[b]) : expf(logp - a.behav_logp[slot]);
         const float s1 = w * A;
         const float wc = fminf(fmaxf(w, 1.f - a.eps_lo), 1.f + a.eps_hi);
         const float s2 = wc * A;
         const float J = fminf(s1, s2);
-        const float dJ = s1 <= s2 ? s1 : 0.f;
+        float dJ = s1 <= s2 ? s1 : 0.f;
+        if (a.seq_expo && a.ratio_level == 1) dJ *= (float)a.seq_len[b];
         float k3 = 0.f, dk3 = 0.f;
         if (a.ref_logp != nullptr) {
           const float rho = a.ref_logp[slot] - logp;
@@ -643,6 +671,13 @@ void launch_seq_weights(const uint8_t* mask, const int32_t* targets, const int32
   hipLaunchKernelGGL(k_seq_len, dim3((unsigned)B), dim3(256), 0, stream, mask, targets, T, V, seq_len);
   hipLaunchKernelGGL(k_seq_coef, dim3(1), dim3(1024), 0, stream, seq_len, group_id, seq_kind, B, G, loss_agg,
                      group_count, seq_coef);
+}
+
+void launch_seq_log_ratio(const uint8_t* mask, const int32_t* targets, const float* logp,
+                          const float* behav_logp, int64_t B, int T, int V, int level, float* seq_expo,
+                          hipStream_t stream) {
+  hipLaunchKernelGGL(k_seq_log_ratio, dim3((unsigned)B), dim3(256), 0, stream, mask, targets, logp, behav_logp,
+                     T, V, level, seq_expo);
 }
 
 void launch_zero_unscored(const uint8_t* mask, const int32_t* targets, int64_t N, int V, int d,

@@ -76,6 +76,13 @@ void launch_seq_weights(const uint8_t* mask, const int32_t* targets, const int32
                         int32_t* seq_len, float* seq_coef, int32_t* group_count /*[G] scratch*/,
                         hipStream_t stream);
 
+// Response-level log-ratio (App. G.1): seq_expo[b] = sum over the scored tokens of sequence b of
+// (logp - behav_logp), divided by the number of scored tokens when level == 2.  Fixed-order
+// reduction, one workgroup per sequence.
+void launch_seq_log_ratio(const uint8_t* mask, const int32_t* targets, const float* logp,
+                          const float* behav_logp, int64_t B, int T, int V, int level, float* seq_expo,
+                          hipStream_t stream);
+
 // Zero out_logp (and out_lse, dH rows) of unscored slots.
 void launch_zero_unscored(const uint8_t* mask, const int32_t* targets, int64_t N, int V, int d,
                           float* out_logp, float* out_lse, void* dH, int dh_elem_bytes,
@@ -99,6 +106,8 @@ struct RowEpiArgs {
   // loss inputs (all nullptr for the log-prob-only entry point)
   const float* behav_logp; const float* ref_logp; const float* seq_adv;
   const float* seq_coef; const uint8_t* seq_kind; int T;
+  // response-level ratio (App. G.1): exponent per sequence, lengths, level 1 (sum) or 2 (mean); null = token ratio
+  const float* seq_expo; const int32_t* seq_len; int ratio_level;
   float eps_lo, eps_hi, beta, lambda;
   float* out_logp; float* out_lse;  // per slot
   float* lse_c; float* g_c;         // per compacted row (nullptr to skip)

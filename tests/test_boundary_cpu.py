@@ -111,6 +111,8 @@ def test_loss_argument_errors():
     assert _loss(_cfg(clip_eps_low=-0.1)) == -7
     assert _loss(_cfg(kl_beta=-1.0)) == -7
     assert _loss(_cfg(loss_agg=2)) == -7
+    assert _loss(_cfg(ratio_level=3)) == -7
+    assert _loss(_cfg(ratio_level=1, loss_agg=1)) == -7
     assert _loss(_cfg(accumulate_dw=3)) == -7
     assert _loss(_cfg(dh_dtype=5)) == -7
     assert _loss(_cfg(chunk_rows=300)) == -7

@@ -29,7 +29,7 @@ def _gpu_adv(mrl, batch, mode=1, **kw):
 
 
 def _run_both(mrl, synth, sp, chunk_rows=256, dh_dtype=None, logp_tol=util.LOGP_TOL, rel_tol=util.REL_TOL,
-              adv_mode=1, h_scale=None, loss_agg=0):
+              adv_mode=1, h_scale=None, loss_agg=0, ratio_level=0, behav_jitter=None):
     batch = synth.make(sp, "cuda")
     if h_scale is not None:
         batch["H"] = (batch["H"].float() * h_scale).to(batch["H"].dtype)
@@ -37,7 +37,11 @@ def _run_both(mrl, synth, sp, chunk_rows=256, dh_dtype=None, logp_tol=util.LOGP_
         g = torch.Generator("cuda").manual_seed(1)
         batch["behav"] = centre + 0.1 * torch.randn(batch["N"], device="cuda", generator=g)
         batch["ref"] = centre + 0.1 * torch.randn(batch["N"], device="cuda", generator=g)
-    cfg = util.cfg_dict(sp, loss_agg=loss_agg)
+    cfg = util.cfg_dict(sp, loss_agg=loss_agg, ratio_level=ratio_level)
+    if behav_jitter is not None:
+        centre = synth.logp_proxy(batch["H"], batch["W"], batch["targets"])
+        g = torch.Generator("cuda").manual_seed(2)
+        batch["behav"] = centre + behav_jitter * torch.randn(batch["N"], device="cuda", generator=g)
 
     # advantages: HIP vs oracle
     adv_g, mean_g, std_g, flags_g = _gpu_adv(mrl, batch, mode=adv_mode)
@@ -51,11 +55,14 @@ def _run_both(mrl, synth, sp, chunk_rows=256, dh_dtype=None, logp_tol=util.LOGP_
 
     # keep tokens off the clip kinks (decided from the oracle's log-probs)
     first = util.oracle_loss(batch, seq_adv_o, cfg, need_grads=False)
-    batch["behav"] = util.move_off_kinks(batch, first["logp"], sp.clip_eps)
+    if ratio_level == 0:
+        batch["behav"] = util.move_off_kinks(batch, first["logp"], sp.clip_eps)
+    else:
+        batch["behav"] = util.move_off_kinks_seq(batch, first["logp"], sp.clip_eps, ratio_level)
     want = util.oracle_loss(batch, seq_adv_o, cfg)
 
     lc = mrl.LossConfig(clip_eps_low=sp.clip_eps, clip_eps_high=sp.clip_eps, kl_beta=sp.kl_beta,
-                        sgt_lambda=sp.sgt_lambda, loss_agg=loss_agg, chunk_rows=chunk_rows,
+                        sgt_lambda=sp.sgt_lambda, loss_agg=loss_agg, chunk_rows=chunk_rows, ratio_level=ratio_level,
                         dh_dtype=(mrl.F32 if sp.dtype == torch.float32 else mrl.BF16) if dh_dtype is None else dh_dtype)
     got = mrl.grpo_loss_fwd_bwd(batch["H"], batch["W"], batch["targets"], batch["mask"].reshape(-1),
                                 batch["behav"], batch["ref"], seq_adv, batch["seq_group"], batch["seq_kind"],
@@ -132,3 +139,20 @@ def test_peaked_softmax(mrl, synth):
 def test_global_token_mean_and_batch_zn(mrl, synth):
     sp = synth.spec(2, n_prompts=3, T=20, V=1500, d=128)
     _run_both(mrl, synth, sp, chunk_rows=256, adv_mode=2, loss_agg=1)
+
+
+@pytest.mark.parametrize("level,idx,over,jitter", [
+    (1, 2, dict(n_prompts=3, T=40, V=2500), 0.03),     # summed log-ratio: small token jitter keeps responses near the band
+    (2, 2, dict(n_prompts=3, T=40, V=2500), 0.8),      # per-token mean: large jitter to reach the band edges
+    (1, 4, dict(n_prompts=5, T=16, V=1000), 0.05),     # with SGT auxiliary rows
+    (2, 1, dict(), 2.0),                               # fp32 sanity path
+])
+def test_response_level_ratio(mrl, synth, level, idx, over, jitter):
+    """Eq. (1) with the response-level ratio of App. G.1; responses span several 256-row passes."""
+    sp = synth.spec(idx, **over)
+    f32 = sp.dtype == torch.float32
+    batch, got, want, st = _run_both(mrl, synth, sp, chunk_rows=0 if f32 else 256, ratio_level=level,
+                                     behav_jitter=jitter, logp_tol=util.F32_LOGP_TOL if f32 else util.LOGP_TOL,
+                                     rel_tol=util.F32_REL_TOL if f32 else util.REL_TOL)
+    # the clip is exercised on both sides of the band or at least on one
+    assert 0 < st["n_clipped_tokens"] < st["n_scored_tokens"]

@@ -57,6 +57,26 @@ def move_off_kinks(batch, oracle_logp, eps, margin=4e-3, shift=0.03):
     return torch.tensor(behav, dtype=torch.float32, device=batch["behav"].device)
 
 
+def move_off_kinks_seq(batch, oracle_logp, eps, level, margin=2e-2, shift=0.08):
+    """Response-level ratios (App. G.1): shifts the behaviour log-prob of the first scored token
+    of every response whose ratio sits within `margin` (in log space) of a clip edge, so that fp32
+    and fp64 take the same clip decision.  Uses the oracle's log-probs only."""
+    B, T = batch["B"], batch["T"]
+    behav = batch["behav"].detach().cpu().numpy().astype(np.float64).reshape(B, T)
+    m = batch["mask"].cpu().numpy().astype(bool).reshape(B, T)
+    lp = np.asarray(oracle_logp).reshape(B, T)
+    for b in range(B):
+        L = int(m[b].sum())
+        if L == 0:
+            continue
+        expo = float(np.sum((lp[b] - behav[b])[m[b]])) / (L if level == 2 else 1)
+        for edge in (np.log1p(-eps), np.log1p(eps)):
+            if abs(expo - edge) < margin:
+                first = int(np.nonzero(m[b])[0][0])
+                behav[b, first] -= shift * (L if level == 2 else 1)
+    return torch.tensor(behav.reshape(-1), dtype=torch.float32, device=batch["behav"].device)
+
+
 def rel_fro(x, ref):
     x = np.asarray(x, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
