@@ -145,3 +145,32 @@ def test_config5_full_size_sampled():
     mrl, sp, b, seq_adv, out, st, n_scored = _run_full(5)
     mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
     _check_properties(sp, b, out, st, n_scored, mflat)
+
+
+def test_config5_scoring_pass_full_size_sampled():
+    """Forward-only scoring pass (log-prob, lse, entropy) on configuration 5 as bench.py runs it:
+    sampled scored rows against the oracle, and size-independent properties for all rows."""
+    import paper_2605_07244_amd as mrl
+    from paper_2605_07244_amd import synth
+    sp = synth.spec(5)
+    b = synth.make(sp, "cuda")
+    mask = b["mask"].reshape(-1)
+    lp, lse, ent = mrl.token_scores(b["H"], b["W"], b["targets"], mask)
+    torch.cuda.synchronize()
+    m = mask.bool()
+    assert torch.all(lp[~m] == 0) and torch.all(lse[~m] == 0) and torch.all(ent[~m] == 0)
+    assert not torch.isnan(lp).any() and not torch.isnan(ent).any()
+    # 0 <= H <= log V and log p <= 0 on every scored row
+    assert float(ent[m].min()) >= 0.0 and float(ent[m].max()) <= np.log(sp.V) + 1e-3
+    assert float(lp[m].max()) <= 0.0
+    rng = np.random.default_rng(77)
+    scored_idx = torch.nonzero(m)[:, 0].cpu().numpy()
+    rows = np.unique(np.concatenate([rng.choice(scored_idx, size=N_SAMPLES, replace=False),
+                                     scored_idx[[0, -1]]]))
+    ridx = torch.tensor(rows, device="cuda")
+    Hs, W = util.to_f64(b["H"][ridx]), util.to_f64(b["W"])
+    want_lp, want_lse = orc.token_logprobs(Hs, W, b["targets"][ridx].cpu().numpy())
+    want_ent = orc.token_entropy(Hs, W)
+    assert np.max(np.abs(lp[ridx].cpu().numpy() - want_lp)) <= util.LOGP_TOL
+    assert np.max(np.abs(lse[ridx].cpu().numpy() - want_lse)) <= util.LOGP_TOL
+    assert np.max(np.abs(ent[ridx].cpu().numpy() - want_ent)) <= util.LOGP_TOL
