@@ -28,7 +28,7 @@
  *     between inputs and labels is the caller's business.  No bias, sampling
  *     temperature 1.
  *   - dtype MRL_BF16: hidden / lm_head_w are bfloat16, matrix products run on
- *     the bf16 MFMA units with fp32 accumulation; d must be a multiple of 64.
+ *     the bf16 MFMA units with fp32 accumulation; d must be a multiple of 128 (the K loop of the GEMM kernels runs over pairs of 64-wide panels).
  *     dtype MRL_F32: hidden / lm_head_w are float, plain fp32 arithmetic (a
  *     small-shape sanity path, not tuned); any d >= 1.
  *   - Only gfx950 devices are supported; there is no fallback path.

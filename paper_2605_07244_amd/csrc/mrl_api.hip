@@ -140,7 +140,7 @@ int default_chunk(int64_t N, int dtype) {
 int check_common(int64_t N, int d, int V, int dtype) {
   if (dtype != MRL_F32 && dtype != MRL_BF16) return MRL_ERR_DTYPE;
   if (N < 0 || N > kMaxSlots || d <= 0 || V <= 0) return MRL_ERR_SHAPE;
-  if (dtype == MRL_BF16 && d % 64 != 0) return MRL_ERR_SHAPE;
+  if (dtype == MRL_BF16 && d % 128 != 0) return MRL_ERR_SHAPE;
   if ((int64_t)V > ((int64_t)1 << 24) || d > (1 << 20)) return MRL_ERR_SHAPE;
   return MRL_OK;
 }
@@ -222,7 +222,7 @@ const char* mrl_status_string(int status) {
   switch (status) {
     case MRL_OK: return "ok";
     case MRL_ERR_NULL: return "a required pointer is NULL";
-    case MRL_ERR_SHAPE: return "invalid shape (sizes must be positive; bf16 needs d % 64 == 0)";
+    case MRL_ERR_SHAPE: return "invalid shape (sizes must be positive; bf16 needs d % 128 == 0)";
     case MRL_ERR_DTYPE: return "unknown dtype";
     case MRL_ERR_TARGET_RANGE: return "target id out of range";
     case MRL_ERR_GROUP_RANGE: return "group id out of range";

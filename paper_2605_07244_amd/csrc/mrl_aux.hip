@@ -499,8 +499,8 @@ __global__ __launch_bounds__(256) void k_finalize(const double* parts, int64_t n
 // dz conversion, bf16 path (proof of Prop. 4: grad log pi(a_i) = e_i - pi).  Elementwise and
 // in place: fp16 logits z[i][v] -> bf16 P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)).
 // A block converts CV_ROWS rows x 2048 columns, 16 bytes per thread and row.  Rows from the
-// valid count up to its multiple of 64 and columns from V up to Vp are written as zeros
-// (the dW contraction runs over whole 64-row panels, the dH one over whole 256-column tiles).
+// valid count up to its multiple of 128 and columns from V up to Vp are written as zeros
+// (the dW contraction runs over pairs of 64-row panels, the dH one over whole 256-column tiles).
 // ----------------------------------------------------------------------------
 constexpr int CV_ROWS = 8, CV_COLS = 2048;
 __global__ __launch_bounds__(256) void k_convert_bf16(uint16_t* ZP, int64_t ldz, const float* lse_c,
@@ -508,7 +508,7 @@ __global__ __launch_bounds__(256) void k_convert_bf16(uint16_t* ZP, int64_t ldz,
                                                       const int32_t* row_index, const int64_t* n_scored,
                                                       int64_t chunk_start, int chunk_rows, int V, int Vp) {
   const int nvalid = valid_rows(n_scored, chunk_start, chunk_rows);
-  const int nzero = (nvalid + 63) / 64 * 64 < chunk_rows ? (nvalid + 63) / 64 * 64 : chunk_rows;
+  const int nzero = (nvalid + 127) / 128 * 128 < chunk_rows ? (nvalid + 127) / 128 * 128 : chunk_rows;
   const int i0 = blockIdx.y * CV_ROWS;
   if (i0 >= nzero) return;
   const int vbase = blockIdx.x * CV_COLS + threadIdx.x * 8;
@@ -592,7 +592,8 @@ __global__ __launch_bounds__(256) void k_transpose_b16(const uint16_t* in, int64
   if (n_scored != nullptr) nrows = valid_rows(n_scored, chunk_start, chunk_rows);
   const int64_t r0 = (int64_t)blockIdx.y * 64;
   const int c0 = blockIdx.x * 64;
-  if (n_scored != nullptr && r0 >= (nrows + 63) / 64 * 64) return;
+  // gathered rows: zero fill up to the multiple of 128 the dW contraction runs over, nothing beyond
+  if (n_scored != nullptr && r0 >= (nrows + 127) / 128 * 128) return;
   const int tc = threadIdx.x & 7, tr = threadIdx.x >> 3;
 #pragma unroll
   for (int k = 0; k < 2; ++k) {

@@ -43,6 +43,9 @@ constexpr int NTHREADS = 256;
 #ifndef RD_GROUPS
 #define RD_GROUPS 7         // MFMA groups (after the first) over which the 8 fragment pairs of the next K step are read
 #endif
+#ifndef CHAIN2
+#define CHAIN2 1            // 1: the two K steps of an accumulator back to back (see the main loop)
+#endif
 #ifndef PF_DIST
 #define PF_DIST 3           // L2 prefetch distance in K panels (0 = off)
 #endif
@@ -163,7 +166,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   int M = p.M, N = p.N, K = p.K;
   if (MODE == MODE_FWD) N = nvalid;
   if (MODE == MODE_DH) M = nvalid;
-  if (MODE == MODE_DW) { int kv = (nvalid + BK - 1) / BK * BK; K = kv < K ? kv : K; }
+  if (MODE == MODE_DW) { int kv = (nvalid + 2 * BK - 1) / (2 * BK) * (2 * BK); K = kv < K ? kv : K; }
   if (MODE == MODE_FWD && nvalid == 0) return;
   if (MODE == MODE_DH && nvalid == 0) return;
   if (MODE == MODE_DW && nvalid == 0 && !p.overwrite) return;
@@ -310,6 +313,101 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
+#if CHAIN2
+  // Software pipeline.  Panel kt+1 is loaded during the MFMAs of panel kt (double buffer).
+  // A panel is 8 groups; group g multiplies the A fragments of 16-row block g (both 32-wide
+  // K steps) with the panel's 16 B fragments: 16 MFMAs, the two K steps of an accumulator back
+  // to back.  Keeping an accumulator for two consecutive MFMAs costs measurably less energy than
+  // touching 64 different ones in turn (about 5 % more FLOP/s from an MFMA-only loop at the
+  // power limit), which is what bounds these kernels on real data.
+  // Registers: the B fragments of a whole panel stay resident, in two sets (this panel / the
+  // next one); A fragments sit in a ring of four pairs and are read four groups ahead, at the end
+  // of the group that used the ring slot.  So the last read of panel kt's LDS slot is issued in
+  // group 3; the barrier after group 4 releases that slot and publishes panel kt+1 (whose loads
+  // were issued in groups 4-7 of panel kt-1); groups 4-6 then read the next B set and groups 4-7
+  // issue the direct loads of panel kt+2 into the released slot, each in the shadow of a group's
+  // MFMAs.
+  // The loop body (two panels, so that the B sets have fixed registers) is branch-free; the last
+  // one or two panels are peeled, and loads that would run past the end re-fetch the last panel
+  // into a slot nobody reads.
+  bf16x8 fbx[2][2][8];   // [set][K step][16-column block]
+  bf16x8 fax[4][2];      // [ring slot][K step]
+  auto read_b = [&](int st, int ks, int j) -> bf16x8 {
+    return *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks] + j * 2048);
+  };
+  auto issue_range = [&](int kt, int slot, int j0, int j1) {
+#pragma unroll
+    for (int j = j0; j < j1; ++j) {
+      const uint32_t st = slot * STAGE_BYTES + wave_lds + (j >> 1) * 1024;
+      if (j & 1) load_lds16(b_ptr[j >> 1] + kt * BK, st + TILE_BYTES);
+      else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st);
+    }
+  };
+  auto panel = [&](int set, int st_cur, int st_nxt, int kt_load, int slot_load, int kt_pre) {
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        mfma16(acc[g][j], fax[g & 3][0], fbx[set][0][j]);
+        mfma16(acc[g][j], fax[g & 3][1], fbx[set][1][j]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (g == 4) {
+        // this thread's part of panel kt+1 has landed (loads complete in order: only the prefetch
+        // issued after them may still be in flight), then everyone's; every wave has issued its
+        // last read of panel kt's slot a group ago, so the slot can be refilled
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(PF_PENDING));
+        PROBE_BAR(__syncthreads());
+      }
+      if (g < 4) {
+        PROBE_RD(fax[g & 3][0] = read_a(st_cur, 0, g + 4));
+        PROBE_RD(fax[g & 3][1] = read_a(st_cur, 1, g + 4));
+      } else {
+        PROBE_RD(fax[g & 3][0] = read_a(st_nxt, 0, g - 4));
+        PROBE_RD(fax[g & 3][1] = read_a(st_nxt, 1, g - 4));
+      }
+      if (g >= 4) {
+        // next B set in groups 4-6: column blocks 0-2, 3-5, 6-7, so that the last of them are
+        // issued a whole group before the next panel starts; direct loads of the panel after
+        // next, four per group
+        if (g < 7) {
+#pragma unroll
+          for (int j = (g - 4) * 3; j < (g == 6 ? 8 : (g - 3) * 3); ++j) {
+            PROBE_RD(fbx[set ^ 1][0][j] = read_b(st_nxt, 0, j));
+            PROBE_RD(fbx[set ^ 1][1][j] = read_b(st_nxt, 1, j));
+          }
+        }
+        PROBE_LD(issue_range(kt_load, slot_load, (g - 4) * 4, (g - 3) * 4));
+        if (PF_DIST > 0 && g == 7) { PROBE_LD(prefetch(kt_pre)); }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto last_k = [&](int k) { return k < nk ? k : nk - 1; };
+  // The number of panels is even (the launchers see to it), so that the two-panel body is the
+  // only code that touches the accumulators: there is no peeled tail whose different register
+  // assignment would make the compiler move accumulators around next to MFMAs it cannot see
+  // into.  The last two panels read ahead and load like any other (the panel after the last is
+  // a re-fetch of the last one, read into registers nobody uses).
+  if (nk > 0) {
+    issue_loads(0, 0, 0, 8);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __syncthreads();
+    issue_range(last_k(1), 1, 0, 16);
+    // keeps the invariant of the loop: one prefetch follows the last load of every panel
+    if (PF_PENDING) prefetch(last_k(PF_DIST));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { fbx[0][0][j] = read_b(0, 0, j); fbx[0][1][j] = read_b(0, 1, j); }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { fax[i][0] = read_a(0, 0, i); fax[i][1] = read_a(0, 1, i); }
+    for (int kt = 0; kt < nk; kt += 2) {
+      panel(0, 0, STAGE_BYTES, last_k(kt + 2), 0, last_k(kt + PF_DIST));
+      panel(1, STAGE_BYTES, 0, last_k(kt + 3), 1, last_k(kt + 1 + PF_DIST));
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
+    drain_mfma(acc[7]);
+  }
+#else
   bf16x8 fa0[8], fb0[8], fa1[8], fb1[8];   // fragments of the two K steps of a panel
 
   // Software pipeline.  Panel kt+1 is loaded during the MFMAs of panel kt (double buffer).
@@ -399,6 +497,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
     drain_mfma(acc[7]);
   }
+
+#endif
 
 #ifdef PROBE_CLOCK
   if (blockIdx.x == 8 && threadIdx.x == 0) { g_probe_clk[0] = clock64() - c0; g_probe_clk[1] = wall_clock64() - w0; }

@@ -36,7 +36,7 @@ void launch_gemm_dh_bf16(const void* P, int64_t ldp, const void* Wt, int64_t ldw
                          const int32_t* row_index, const int64_t* n_scored, int64_t chunk_start,
                          int chunk_rows, int Vp, int d, void* dH, int dh_f32, hipStream_t stream);
 
-// dW: A = P^T read in place from P [chunk_rows, Vp] (rows >= valid rows rounded up to 64 and
+// dW: A = P^T read in place from P [chunk_rows, Vp] (rows >= valid rows rounded up to 128 and
 // columns >= V must be zero), B = Ht [d, chunk_rows]; dW[v, :] = (or +=) sum over the
 // chunk's valid rows.  overwrite = 1 stores, 0 adds into the existing values.
 void launch_gemm_dw_bf16(const void* P, int64_t ldp, const void* Ht, int64_t ldht,
@@ -119,7 +119,7 @@ void launch_row_epilogue(const RowEpiArgs& a, hipStream_t stream);
 
 // dz conversion: reads the chunk's logits (fp16 for the bf16 path, float for fp32),
 // writes P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)) in place (same element size); rows from
-// the valid count up to its multiple of 64 and columns >= V become zero.  The fp32 path also
+// the valid count up to its multiple of 128 and columns >= V become zero.  The fp32 path also
 // writes the transpose Pt[v][i] (Pt is unused, and may be null, for bf16).
 void launch_convert(void* ZP, int64_t ldz, void* Pt, int64_t ldpt, const float* lse_c,
                     const float* g_c, const int32_t* targets, const int32_t* row_index,

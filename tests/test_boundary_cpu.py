@@ -50,17 +50,17 @@ def _cfg(**kw):
 def test_token_logprobs_argument_errors():
     lib = m.lib()
     f = lib.mrl_token_logprobs
-    assert f(None, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -1
-    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, None, None, FAKE, 1 << 20, None) == -1
+    assert f(None, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -1
+    assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, None, None, FAKE, 1 << 20, None) == -1
     assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 7, FAKE, None, FAKE, 1 << 20, None) == -3
-    assert f(FAKE, FAKE, FAKE, None, -1, 64, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2
+    assert f(FAKE, FAKE, FAKE, None, -1, 128, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2
     assert f(FAKE, FAKE, FAKE, None, 8, 0, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2
     assert f(FAKE, FAKE, FAKE, None, 8, 64, 0, 1, FAKE, None, FAKE, 1 << 20, None) == -2
-    assert f(FAKE, FAKE, FAKE, None, 8, 72, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2   # bf16: d % 64
-    assert f(FAKE, FAKE, FAKE, None, 0, 64, 32, 1, FAKE, None, None, 0, None) == 0          # N = 0: no-op
-    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, None, 0, None) == -6
-    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, P(0x1001), 1 << 20, None) == -6  # misaligned
-    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, FAKE, 16, None) == -6           # too small
+    assert f(FAKE, FAKE, FAKE, None, 8, 72, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2   # bf16: d % 128
+    assert f(FAKE, FAKE, FAKE, None, 0, 128, 32, 1, FAKE, None, None, 0, None) == 0          # N = 0: no-op
+    assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, None, 0, None) == -6
+    assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, P(0x1001), 1 << 20, None) == -6  # misaligned
+    assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, FAKE, 16, None) == -6           # too small
 
 
 def test_workspace_queries():
@@ -89,7 +89,7 @@ def test_group_advantages_argument_errors():
     assert f(FAKE, FAKE, None, None, None, 0, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == 0
 
 
-def _loss(cfg, *, hidden=FAKE, ref=FAKE, B=4, T=8, G=2, d=64, V=100, dt=1, ws=FAKE, ws_bytes=1 << 30,
+def _loss(cfg, *, hidden=FAKE, ref=FAKE, B=4, T=8, G=2, d=128, V=100, dt=1, ws=FAKE, ws_bytes=1 << 30,
           stats=FAKE, seq_adv=FAKE):
     f = m.lib().mrl_grpo_loss_fwd_bwd
     return f(hidden, FAKE, FAKE, FAKE, FAKE, ref, seq_adv, FAKE, None, B, T, G, d, V, dt,
@@ -163,9 +163,9 @@ def test_thl_word_align_argument_errors():
 def test_token_scores_argument_errors():
     lib = m.lib()
     f = lib.mrl_token_scores
-    assert f(None, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, None, FAKE, 1 << 20, None) == -1
+    assert f(None, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, None, FAKE, 1 << 20, None) == -1
     assert f(FAKE, FAKE, FAKE, None, 8, 72, 32, 1, FAKE, None, FAKE, FAKE, 1 << 20, None) == -2
-    assert f(FAKE, FAKE, FAKE, None, 8, 64, 32, 1, FAKE, None, FAKE, FAKE, 16, None) == -6    # workspace too small
-    assert f(FAKE, FAKE, FAKE, None, 0, 64, 32, 1, FAKE, None, FAKE, None, 0, None) == 0
+    assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, FAKE, FAKE, 16, None) == -6    # workspace too small
+    assert f(FAKE, FAKE, FAKE, None, 0, 128, 32, 1, FAKE, None, FAKE, None, 0, None) == 0
     # the entropy needs a third partial buffer: its workspace is the larger one
     assert lib.mrl_token_scores_workspace(4096, 256, 4000, 1) > lib.mrl_token_logprobs_workspace(4096, 256, 4000, 1)

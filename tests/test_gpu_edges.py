@@ -152,7 +152,7 @@ def test_too_small_hint_is_reported_not_silent(mrl, synth):
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 def test_token_logprobs_entry_point(mrl, synth, dtype):
-    sp = synth.spec(2, n_prompts=2, T=40, V=2700, d=192, dtype=dtype)
+    sp = synth.spec(2, n_prompts=2, T=40, V=2700, d=384, dtype=dtype)
     b = synth.make(sp, "cuda")
     H, W, y = util.to_f64(b["H"]), util.to_f64(b["W"]), b["targets"].cpu().numpy()
     want_lp, want_lse = orc.token_logprobs(H, W, y)
@@ -240,7 +240,7 @@ def test_mfma_rate_probe(mrl):
 def test_token_scores_entropy(mrl, synth, dtype, scale):
     """Forward-only scoring pass with the entropy output against the oracle: several vocabulary
     tiles with a ragged last one, masked rows, and a peaked softmax (hidden states scaled by 8)."""
-    sp = synth.spec(2, n_prompts=2, T=40, V=2700, d=192, dtype=dtype)
+    sp = synth.spec(2, n_prompts=2, T=40, V=2700, d=384, dtype=dtype)
     b = synth.make(sp, "cuda")
     Hs = (b["H"].float() * scale).to(dtype)
     H, W, y = util.to_f64(Hs), util.to_f64(b["W"]), b["targets"].cpu().numpy()
