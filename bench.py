@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-rows", type=int, default=0)
     ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (debug)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the legs that are not part of `value` (alignment pass, forward-only scoring pass); "
+                         "used for kernel profiles so that only the step's launches are in the trace")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (calibration of the HBM traffic counters)")
     args = ap.parse_args()
@@ -230,22 +233,24 @@ def main():
     measured_peak["pct_of_random_operand_rate"] = round(
         100.0 * tokens_per_s * flop_per_token / (measured_peak["random_operands"] * 1e12), 2)
 
-    thl_leg = thl_alignment_leg(mrl, synth, torch, with_cpu=not args.no_cpu_baseline)
+    thl_leg = None if args.no_extras else thl_alignment_leg(mrl, synth, torch, with_cpu=not args.no_cpu_baseline)
 
-    # forward-only scoring pass (behaviour / reference traces, re-scoring of pooled peer rollouts):
-    # log-probs + entropy of the same batch, 2 N d V FLOP
-    ws_f = torch.empty(mrl.lib().mrl_token_scores_workspace(N, d, V, mrl.BF16), dtype=torch.uint8, device="cuda")
-    mrl.token_scores(batch["H"], batch["W"], batch["targets"], mask, workspace=ws_f)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(2):
+    fwd_leg = None
+    if not args.no_extras:
+        # forward-only scoring pass (behaviour / reference traces, re-scoring of pooled peer rollouts):
+        # log-probs + entropy of the same batch, 2 N d V FLOP
+        ws_f = torch.empty(mrl.lib().mrl_token_scores_workspace(N, d, V, mrl.BF16), dtype=torch.uint8, device="cuda")
         mrl.token_scores(batch["H"], batch["W"], batch["targets"], mask, workspace=ws_f)
-    torch.cuda.synchronize()
-    dt_f = (time.perf_counter() - t0) / 2
-    del ws_f
-    fwd_leg = dict(outputs="logp, lse, entropy", ms_per_call=round(1e3 * dt_f, 2),
-                   tokens_per_s=round(n_scored / dt_f, 1),
-                   pct_bf16_mfma_peak=round(100.0 * 2.0 * n_scored * d * V / dt_f / (MFMA_BF16_PEAK_TFLOPS * 1e12), 2))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(2):
+            mrl.token_scores(batch["H"], batch["W"], batch["targets"], mask, workspace=ws_f)
+        torch.cuda.synchronize()
+        dt_f = (time.perf_counter() - t0) / 2
+        del ws_f
+        fwd_leg = dict(outputs="logp, lse, entropy", ms_per_call=round(1e3 * dt_f, 2),
+                       tokens_per_s=round(n_scored / dt_f, 1),
+                       pct_bf16_mfma_peak=round(100.0 * 2.0 * n_scored * d * V / dt_f / (MFMA_BF16_PEAK_TFLOPS * 1e12), 2))
 
     base = None
     if not args.no_cpu_baseline:
