@@ -37,15 +37,6 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
-#ifndef LD_GROUPS
-#define LD_GROUPS 8         // MFMA groups (of 16 per K panel) over which a panel's 16 direct loads are spread
-#endif
-#ifndef RD_GROUPS
-#define RD_GROUPS 7         // MFMA groups (after the first) over which the 8 fragment pairs of the next K step are read
-#endif
-#ifndef CHAIN2
-#define CHAIN2 1            // 1: the two K steps of an accumulator back to back (see the main loop)
-#endif
 #ifndef PF_DIST
 #define PF_DIST 3           // L2 prefetch distance in K panels (0 = off)
 #endif
@@ -313,7 +304,6 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
-#if CHAIN2
   // Software pipeline.  Panel kt+1 is loaded during the MFMAs of panel kt (double buffer).
   // A panel is 8 groups; group g multiplies the A fragments of 16-row block g (both 32-wide
   // K steps) with the panel's 16 B fragments: 16 MFMAs, the two K steps of an accumulator back
@@ -407,98 +397,6 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
     drain_mfma(acc[7]);
   }
-#else
-  bf16x8 fa0[8], fb0[8], fa1[8], fb1[8];   // fragments of the two K steps of a panel
-
-  // Software pipeline.  Panel kt+1 is loaded during the MFMAs of panel kt (double buffer).
-  // A panel is two 32-wide K steps of 8 groups; a group multiplies one A fragment with the
-  // eight B fragments (8 MFMAs, the A operand stays put) and meanwhile reads one A and one B
-  // fragment of the next K step.  The barrier that publishes panel kt+1 (and frees the slot
-  // of panel kt, whose last fragments are in registers by then) sits between the two K steps,
-  // so the LDS latency of the next panel's first fragments is covered by the second K step.
-  // Counted from that barrier, the 16 direct loads of the panel after next are spread over
-  // the first LD_GROUPS groups, each issued in the shadow of a group's MFMAs.
-  // The loop body is branch-free (a branch inside it splits the accumulator live ranges
-  // and makes the register allocator spill): the last panel is peeled, and the loads that
-  // would run past the end re-fetch the last panel into a slot nobody reads.
-  auto issue_group = [&](int kt, int slot, int g) {
-#pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if (j * LD_GROUPS / 16 == g) {
-        const uint32_t st = slot * STAGE_BYTES + wave_lds + (j >> 1) * 1024;
-        if (j & 1) load_lds16(b_ptr[j >> 1] + kt * BK, st + TILE_BYTES);
-        else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st);
-      }
-  };
-  // one K step: multiply fragments (ca, cb); meanwhile read K step ks_next of the panel at LDS
-  // offset st into (na, nb) (skipped if ks_next < 0) and issue load groups g0 .. g0+7
-  auto kstep = [&](const bf16x8* ca, const bf16x8* cb, bf16x8* na, bf16x8* nb, int st, int ks_next,
-                   int kt_load, int slot_load, int g0, int kt_pre) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      // fragment reads of the next K step: none in the first group (the wait for the current
-      // fragments sits there and would otherwise cover fresh reads as well), then pair r in
-      // group 1 + r * RD_GROUPS / 8, so that the last ones are issued several groups before
-      // the wait that precedes their use
-      if (ks_next >= 0) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-          if (1 + r * RD_GROUPS / 8 == i) {
-            PROBE_RD(na[r] = read_a(st, ks_next & 1, r));
-            PROBE_RD(nb[r] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks_next & 1] + r * 2048));
-          }
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        mfma16(acc[i][j], ca[i], cb[j]);
-      __builtin_amdgcn_sched_barrier(0);
-      if (g0 >= 0) {
-        PROBE_LD(issue_group(kt_load, slot_load, g0 + i));
-        if (PF_DIST > 0 && g0 + i == LD_GROUPS - 1) { PROBE_LD(prefetch(kt_pre)); }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  auto read_frags = [&](bf16x8* af, bf16x8* bfr, int st, int ks) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      af[i] = read_a(st, ks, i);
-      bfr[i] = *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks] + i * 2048);
-    }
-  };
-  if (nk > 0) {
-    issue_loads(0, 0, 0, 8);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < 8; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);
-#ifdef PROBE_NOGLOAD
-    for (int g = 8; g < 16; ++g) issue_group(nk > 1 ? 1 : 0, 1, g);   // both slots hold real data
-#endif
-    // keeps the invariant of the loop: one prefetch follows the last load of every panel
-    if (PF_PENDING && LD_GROUPS <= 8) prefetch(PF_DIST < nk ? PF_DIST : nk - 1);
-    read_frags(fa0, fb0, 0, 0);
-  }
-  for (int kt = 0; kt < nk - 1; ++kt) {
-    const int st0 = (kt & 1) * STAGE_BYTES, st1 = STAGE_BYTES - st0;
-    const int kpre = kt + PF_DIST < nk ? kt + PF_DIST : nk - 1;
-    kstep(fa0, fb0, fa1, fb1, st0, 1, kt + 1, (kt + 1) & 1, 8, kpre);
-    // this thread's part of panel kt+1 has landed (loads complete in order: only the prefetch
-    // issued after them may still be in flight), then everyone's; every wave has finished
-    // reading panel kt (its last fragments are in registers), so its slot can be refilled
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(PF_PENDING));
-    PROBE_BAR(__syncthreads());
-    kstep(fa1, fb1, fa0, fb0, st1, 0, kt + 2 < nk ? kt + 2 : nk - 1, kt & 1, 0, kpre);
-  }
-  if (nk > 0) {
-    const int st0 = ((nk - 1) & 1) * STAGE_BYTES;
-    kstep(fa0, fb0, fa1, fb1, st0, 1, 0, 0, -1, 0);
-    kstep(fa1, fb1, nullptr, nullptr, 0, -1, 0, 0, -1, 0);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
-    drain_mfma(acc[7]);
-  }
-
-#endif
 
 #ifdef PROBE_CLOCK
   if (blockIdx.x == 8 && threadIdx.x == 0) { g_probe_clk[0] = clock64() - c0; g_probe_clk[1] = wall_clock64() - w0; }
