@@ -115,7 +115,7 @@ int mrl_token_scores(const void* hidden /*[N,d] dev*/, const void* lm_head_w /*[
  * (2) Group-relative advantages and the SGT gate.
  *     Sec. 3: rbar = mean of the group's rewards, A~ = r - rbar,
  *     A~zn = A~ / (std + eps).  Sec. 5.1 (PRP): own and peer rollouts of a
- *     prompt form one group and are normalised together.  App. G.1 (XGRPO):
+ *     prompt form one group and are normalised together.  App. I.1 (XGRPO):
  *     the baseline mean / std pool the rewards of every policy while only
  *     own rollouts are scored.  Sec. 5.3 / App. B (SGT): the gate fires for a
  *     prompt when every own rollout failed and some peer succeeded.
@@ -128,6 +128,11 @@ int mrl_token_scores(const void* hidden /*[N,d] dev*/, const void* lm_head_w /*[
  * std uses divisor (count - ddof), ddof in {0, 1}; std = 0 if count <= ddof.
  * mix_alpha in [0, 1]: A = (1 - alpha) * A_own + alpha * A_pool, where A_own
  * uses statistics over (in_stats & is_own) entries only; 1 = pooled rule.
+ * baseline_shift (NULL = none): baseline_shift[g] is added to the per-prompt baseline
+ * of group g, its pooled and its own-only mean alike, before the rewards are centred;
+ * the std stays that of the unshifted rewards and out_group_mean reports the unshifted
+ * pooled mean.  It is the perturbed-baseline control of App. C.4 (shared-normalisation
+ * ablation); the caller draws the perturbations.
  * An entry whose group id is outside [0, G) gets advantage 0 and enters no
  * statistic.  Sums are accumulated in fp64 in a fixed order (bit-reproducible).
  * Optional outputs (NULL to skip): out_group_mean / out_group_std (pooled
@@ -137,6 +142,7 @@ int mrl_group_advantages(const float* rewards /*[B] dev*/, const int32_t* group_
                          const uint8_t* in_stats /*[B] dev | NULL*/,
                          const uint8_t* scored /*[B] dev | NULL*/,
                          const uint8_t* is_own /*[B] dev | NULL*/,
+                         const float* baseline_shift /*[G] dev | NULL*/,
                          int64_t B, int32_t G, int32_t adv_mode, float eps_norm, int32_t ddof,
                          float mix_alpha, float neg_thresh, float pos_thresh,
                          float* out_adv /*[B] dev*/, float* out_group_mean /*[G] dev | NULL*/,
@@ -184,9 +190,9 @@ typedef struct {
   int32_t ratio_level;   /* which importance ratio enters Eq. (1):
                             0 = per token, w_t = exp(l_t - l_beh,t)                (Sec. 3)
                             1 = per response, exp{L_theta - L_behavior}, L = sums over the
-                                response's scored tokens                           (App. G.1)
+                                response's scored tokens                           (App. I.1)
                             2 = per response, exp of the per-token mean of the same sum (the
-                                magnitudes of App. F's sequence-ratio table are those of a mean)
+                                magnitudes of App. E.3's sequence-ratio table are those of a mean)
                             Levels 1 and 2 need loss_agg = 0; the KL term stays per token; the
                             ratio statistics then count each token with its response's ratio.
                             They run the forward contraction twice (the response sums must be

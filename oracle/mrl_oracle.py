@@ -14,9 +14,9 @@ Citations are to the paper's sections / equations:
     w = exp(l_theta - l_old), group-relative advantages, Eq. (1) (the clipped
     surrogate plus beta * R(theta)).
   * Sec. 5.1 (PRP): pool-wide advantage normalisation, behaviour denominator.
-  * App. G.1 (XGRPO paragraph): pooled mean / std baseline.
+  * App. I.1 (XGRPO paragraph): pooled mean / std baseline.
   * Sec. 5.3, Eq. (2), App. B (SGT): gate, auxiliary NLL, lambda weighting.
-  * App. G, proof of Prop. 4: grad log pi(a_i) = e_i - pi for a softmax.
+  * App. I, proof of Prop. 4: grad log pi(a_i) = e_i - pi for a softmax.
 
 Readings of points the paper leaves open (each is listed in the design notes):
   * R(theta) is the k3 estimator exp(rho) - rho - 1, rho = l_ref - l_theta,
@@ -29,7 +29,7 @@ Readings of points the paper leaves open (each is listed in the design notes):
 
 Parity status: every function here is pinned by tests/test_oracle_pins.py
 except the XGRPO alpha-mix with alpha strictly between 0 and 1, whose rule the
-paper does not print ("parity unpinned" for that setting only).
+paper does not print; the blend as read is pinned, the reading is not.
 """
 from __future__ import annotations
 
@@ -98,7 +98,7 @@ def token_entropy(H, W, token_mask=None):
 
 
 # --------------------------------------------------------------------------
-# Sec. 3 advantages; Sec. 5.1 pool-wide; App. G.1 pooled baseline; SGT gate
+# Sec. 3 advantages; Sec. 5.1 pool-wide; App. I.1 pooled baseline; SGT gate
 # --------------------------------------------------------------------------
 def _mean_std(r, ddof):
     k = r.size
@@ -113,18 +113,24 @@ def _mean_std(r, ddof):
 
 def group_advantages(rewards, group_id, G, in_stats=None, scored=None, is_own=None,
                      mode=ADV_GROUP_ZN, eps_norm=1e-6, ddof=0, mix_alpha=1.0,
-                     neg_thresh=0.2, pos_thresh=0.8):
+                     neg_thresh=0.2, pos_thresh=0.8, baseline_shift=None):
     """Group-relative advantages and SGT gate flags.
 
     Stat members of group g are the entries with in_stats = 1; their rewards
     form rbar and std (Sec. 3).  PRP puts own and peer rollouts in the same
     group with in_stats = scored = 1 (Sec. 5.1); XGRPO adds the peers' rewards
     with in_stats = 1, scored = 0, which makes rbar, std the pooled statistics
-    of App. G.1.  Entries with scored = 0 get advantage 0.
+    of App. I.1.  Entries with scored = 0 get advantage 0.
 
     mix_alpha blends own-only statistics (stat members that are also is_own)
     with the pooled ones: A = (1 - alpha) * A_own + alpha * A_pool.  alpha = 1
-    is the pooled rule of App. G.1, alpha = 0 plain per-policy GRPO.
+    is the pooled rule of App. I.1, alpha = 0 plain per-policy GRPO.
+
+    baseline_shift[g] (optional) is added to the per-prompt baseline of group g
+    (its pooled and its own-only mean alike) before the rewards are centred; the
+    standard deviations stay those of the unshifted rewards.  This is the
+    perturbed-baseline control of App. C.4 ("Ablation: shared normalization for
+    XGRPO"); the perturbation values are an input.
 
     Flags per group (Sec. 5.3 gate, thresholds from App. A):
       bit0 all_fail    : every is_own entry has reward < neg_thresh (and one exists)
@@ -146,6 +152,7 @@ def group_advantages(rewards, group_id, G, in_stats=None, scored=None, is_own=No
     mean = np.zeros(G)
     std = np.zeros(G)
     flags = np.zeros(G, dtype=np.uint8)
+    shift = np.zeros(G) if baseline_shift is None else np.asarray(baseline_shift, dtype=np.float64)
 
     def normalise(x, mu, sd):
         if mode == ADV_GROUP_ZN:
@@ -162,11 +169,11 @@ def group_advantages(rewards, group_id, G, in_stats=None, scored=None, is_own=No
         for b in members:
             if not sc[b]:
                 continue
-            a_pool = normalise(r[b], mu_p, sd_p) if pool.size else 0.0
+            a_pool = normalise(r[b], mu_p + shift[g], sd_p) if pool.size else 0.0
             if mix_alpha == 1.0:
                 adv[b] = a_pool
             else:
-                a_own = normalise(r[b], mu_o, sd_o) if own_pool.size else 0.0
+                a_own = normalise(r[b], mu_o + shift[g], sd_o) if own_pool.size else 0.0
                 adv[b] = (1.0 - mix_alpha) * a_own + mix_alpha * a_pool
         own_m = members[own[members]]
         peer_m = members[~own[members]]
@@ -266,12 +273,12 @@ def loss_from_logp(logp, token_mask, behav_logp, ref_logp, seq_adv, group_id, se
       L_pg  = - sum c * J,  L_kl = sum c * k3,  L_sgt = - sum c_sgt * l.
     g = dL/dl = c * (-dJ + beta * dk3) on GRPO rows, -lambda * c_sgt on SGT rows.
     Statistics: a token is "clipped" when its ratio lies outside
-    [1 - eps_lo, 1 + eps_hi] (App. F, token-ratio table caption); it has zero
+    [1 - eps_lo, 1 + eps_hi] (App. E.3, token-ratio table caption); it has zero
     surrogate gradient when s2 < s1.  Means run over scored GRPO tokens.
 
     cfg["ratio_level"] (default 0 = the token ratio of Eq. 1) selects the response-level ratio
-    of App. G.1 instead: 1 = exp of the summed log-ratio, 2 = exp of its per-token mean (the
-    magnitudes of App. F's sequence-ratio table, medians 0.75-0.91 over whole responses, are
+    of App. I.1 instead: 1 = exp of the summed log-ratio, 2 = exp of its per-token mean (the
+    magnitudes of App. E.3's sequence-ratio table, medians 0.75-0.91 over whole responses, are
     those of a per-token mean).  The KL term stays per token.  Statistics then use the
     response's ratio for each of its tokens.
     """
@@ -290,7 +297,7 @@ def loss_from_logp(logp, token_mask, behav_logp, ref_logp, seq_adv, group_id, se
                                             cfg["clip_eps_low"], cfg["clip_eps_high"])
     level = int(cfg.get("ratio_level", 0))
     if level != 0:
-        # Response-level ratio of App. G.1: rho_b = exp{L_theta - L_behavior} with the sums over the
+        # Response-level ratio of App. I.1: rho_b = exp{L_theta - L_behavior} with the sums over the
         # response's scored tokens (level 1), or their per-token mean (level 2); it takes the place
         # of the token ratio in Eq. (1).  Every token of a response then carries the response's J,
         # so E_tok[J] = J_b, and d rho_b / d l_t = rho_b (level 1) or rho_b / L_b (level 2).

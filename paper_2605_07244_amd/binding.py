@@ -89,7 +89,7 @@ def lib() -> ctypes.CDLL:
     L.mrl_token_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32,
                                    c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     L.mrl_group_advantages.restype = c_int
-    L.mrl_group_advantages.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
+    L.mrl_group_advantages.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32,
                                        c_int32, c_float, c_int32, c_float, c_float, c_float,
                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     L.mrl_grpo_loss_workspace.restype = c_size_t
@@ -199,8 +199,10 @@ def token_scores(hidden, lm_head_w, target_ids, token_mask=None, workspace=None,
 
 
 def group_advantages(rewards, group_id, G, in_stats=None, scored=None, is_own=None, mode=ADV_GROUP_ZN,
-                     eps_norm=1e-6, ddof=0, mix_alpha=1.0, neg_thresh=0.2, pos_thresh=0.8):
+                     eps_norm=1e-6, ddof=0, mix_alpha=1.0, neg_thresh=0.2, pos_thresh=0.8, baseline_shift=None):
     """mrl_group_advantages: returns (adv[B], mean[G], std[G], flags[G] uint8)."""
+    if baseline_shift is not None and baseline_shift.numel() != G:
+        raise ValueError("baseline_shift must have G entries")
     B = rewards.numel()
     dev = rewards.device
     adv = torch.empty(B, dtype=torch.float32, device=dev)
@@ -209,7 +211,8 @@ def group_advantages(rewards, group_id, G, in_stats=None, scored=None, is_own=No
     flags = torch.empty(G, dtype=torch.uint8, device=dev)
     rc = lib().mrl_group_advantages(_ptr(rewards, torch.float32, "rewards"), _ptr(group_id, torch.int32, "group_id"),
                                     _ptr(in_stats, torch.uint8, "in_stats"), _ptr(scored, torch.uint8, "scored"),
-                                    _ptr(is_own, torch.uint8, "is_own"), B, G, mode, eps_norm, ddof, mix_alpha,
+                                    _ptr(is_own, torch.uint8, "is_own"),
+                                    _ptr(baseline_shift, torch.float32, "baseline_shift"), B, G, mode, eps_norm, ddof, mix_alpha,
                                     neg_thresh, pos_thresh, _ptr(adv), _ptr(mean), _ptr(std), _ptr(flags), _stream())
     _check(rc, "mrl_group_advantages")
     return adv, mean, std, flags

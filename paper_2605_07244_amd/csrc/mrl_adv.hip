@@ -1,5 +1,5 @@
 // Group-relative advantages (Sec. 3), pool-wide (Sec. 5.1) and pooled-baseline
-// (App. G.1) variants, and the SGT gate flags (Sec. 5.3 / App. B).
+// (App. I.1) variants, and the SGT gate flags (Sec. 5.3 / App. B).
 //
 // One wavefront per group scans all B entries (B is a few thousand: the whole
 // input is a few KB and stays in L2), so group members need not be contiguous
@@ -24,7 +24,7 @@ __device__ inline int wave_sum_i(int x) {
 
 struct AdvArgs {
   const float* rewards; const int32_t* group_id;
-  const uint8_t* in_stats; const uint8_t* scored; const uint8_t* is_own;
+  const uint8_t* in_stats; const uint8_t* scored; const uint8_t* is_own; const float* baseline_shift;
   int64_t B; int G; int mode; float eps_norm; int ddof; float mix_alpha;
   float neg_thresh, pos_thresh;
   float* out_adv; float* out_mean; float* out_std; uint8_t* out_flags;
@@ -68,17 +68,20 @@ __global__ __launch_bounds__(256) void k_group_adv(AdvArgs a) {
   // pass 3: advantages
   const bool zn = a.mode == 1;
   const double eps = (double)a.eps_norm, alpha = (double)a.mix_alpha;
+  // perturbed-baseline control (App. C.4): the shift moves the baseline, not the std
+  const double shift = a.baseline_shift != nullptr ? (double)a.baseline_shift[g] : 0.0;
+  const double bl_p = mu_p + shift, bl_o = mu_o + shift;
   for (int64_t b = lane; b < a.B; b += 64) {
     if (a.group_id[b] != g) continue;
     const bool sc = a.scored == nullptr || a.scored[b] != 0;
     double adv = 0.0;
     if (sc) {
       const double r = (double)a.rewards[b];
-      const double ap = cnt_p > 0 ? (zn ? (r - mu_p) / (sd_p + eps) : r - mu_p) : 0.0;
+      const double ap = cnt_p > 0 ? (zn ? (r - bl_p) / (sd_p + eps) : r - bl_p) : 0.0;
       if (a.mix_alpha == 1.0f) {
         adv = ap;
       } else {
-        const double ao = cnt_o > 0 ? (zn ? (r - mu_o) / (sd_o + eps) : r - mu_o) : 0.0;
+        const double ao = cnt_o > 0 ? (zn ? (r - bl_o) / (sd_o + eps) : r - bl_o) : 0.0;
         adv = (1.0 - alpha) * ao + alpha * ap;
       }
     }
@@ -149,11 +152,11 @@ __global__ __launch_bounds__(1024) void k_adv_batch_scale(const int32_t* group_i
 }  // namespace
 
 void launch_group_advantages(const float* rewards, const int32_t* group_id, const uint8_t* in_stats,
-                             const uint8_t* scored, const uint8_t* is_own, int64_t B, int G,
-                             int mode, float eps_norm, int ddof, float mix_alpha, float neg_thresh,
+                             const uint8_t* scored, const uint8_t* is_own, const float* baseline_shift,
+                             int64_t B, int G, int mode, float eps_norm, int ddof, float mix_alpha, float neg_thresh,
                              float pos_thresh, float* out_adv, float* out_mean, float* out_std,
                              uint8_t* out_flags, hipStream_t stream) {
-  AdvArgs a = {rewards, group_id, in_stats, scored, is_own, B, G, mode, eps_norm, ddof, mix_alpha,
+  AdvArgs a = {rewards, group_id, in_stats, scored, is_own, baseline_shift, B, G, mode, eps_norm, ddof, mix_alpha,
                neg_thresh, pos_thresh, out_adv, out_mean, out_std, out_flags};
   hipLaunchKernelGGL(k_adv_clear_orphans, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, stream, group_id, B,
                      G, out_adv);

@@ -328,8 +328,8 @@ int mrl_token_logprobs(const void* hidden, const void* lm_head_w, const int32_t*
 
 // --------------------------------------------------------------------------- (2)
 int mrl_group_advantages(const float* rewards, const int32_t* group_id, const uint8_t* in_stats,
-                         const uint8_t* scored, const uint8_t* is_own, int64_t B, int32_t G,
-                         int32_t adv_mode, float eps_norm, int32_t ddof, float mix_alpha,
+                         const uint8_t* scored, const uint8_t* is_own, const float* baseline_shift,
+                         int64_t B, int32_t G, int32_t adv_mode, float eps_norm, int32_t ddof, float mix_alpha,
                          float neg_thresh, float pos_thresh, float* out_adv, float* out_group_mean,
                          float* out_group_std, uint8_t* out_flags, void* stream) {
   if (!rewards || !group_id || !out_adv) return MRL_ERR_NULL;
@@ -342,7 +342,7 @@ int mrl_group_advantages(const float* rewards, const int32_t* group_id, const ui
   if (rc != MRL_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   Scope sc(MRL_PROF_ADV, s);
-  launch_group_advantages(rewards, group_id, in_stats, scored, is_own, B, G, adv_mode, eps_norm, ddof,
+  launch_group_advantages(rewards, group_id, in_stats, scored, is_own, baseline_shift, B, G, adv_mode, eps_norm, ddof,
                           mix_alpha, neg_thresh, pos_thresh, out_adv, out_group_mean, out_group_std,
                           out_flags, s);
   return last_error();

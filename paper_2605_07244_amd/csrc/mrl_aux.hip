@@ -402,7 +402,7 @@ __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
       float g;
       if (kind == 0) {
         const float A = a.seq_adv[b];
-        // token ratio of Eq. (1), or the response's ratio (App. G.1) whose derivative with
+        // token ratio of Eq. (1), or the response's ratio (App. I.1) whose derivative with
         // respect to each token's log-prob is rho (summed form) or rho / L_b (mean form)
         const float w = a.seq_expo ? expf(a.seq_expo[b]) : expf(logp - a.behav_logp[slot]);
         const float s1 = w * A;

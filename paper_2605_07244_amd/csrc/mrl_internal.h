@@ -76,7 +76,7 @@ void launch_seq_weights(const uint8_t* mask, const int32_t* targets, const int32
                         int32_t* seq_len, float* seq_coef, int32_t* group_count /*[G] scratch*/,
                         hipStream_t stream);
 
-// Response-level log-ratio (App. G.1): seq_expo[b] = sum over the scored tokens of sequence b of
+// Response-level log-ratio (App. I.1): seq_expo[b] = sum over the scored tokens of sequence b of
 // (logp - behav_logp), divided by the number of scored tokens when level == 2.  Fixed-order
 // reduction, one workgroup per sequence.
 void launch_seq_log_ratio(const uint8_t* mask, const int32_t* targets, const float* logp,
@@ -106,7 +106,7 @@ struct RowEpiArgs {
   // loss inputs (all nullptr for the log-prob-only entry point)
   const float* behav_logp; const float* ref_logp; const float* seq_adv;
   const float* seq_coef; const uint8_t* seq_kind; int T;
-  // response-level ratio (App. G.1): exponent per sequence, lengths, level 1 (sum) or 2 (mean); null = token ratio
+  // response-level ratio (App. I.1): exponent per sequence, lengths, level 1 (sum) or 2 (mean); null = token ratio
   const float* seq_expo; const int32_t* seq_len; int ratio_level;
   float eps_lo, eps_hi, beta, lambda;
   float* out_logp; float* out_lse;  // per slot
@@ -135,8 +135,8 @@ void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, void* 
 
 // Group-relative advantages (Sec. 3) with pooled / own statistics and SGT gate flags.
 void launch_group_advantages(const float* rewards, const int32_t* group_id, const uint8_t* in_stats,
-                             const uint8_t* scored, const uint8_t* is_own, int64_t B, int G,
-                             int mode, float eps_norm, int ddof, float mix_alpha, float neg_thresh,
+                             const uint8_t* scored, const uint8_t* is_own, const float* baseline_shift,
+                             int64_t B, int G, int mode, float eps_norm, int ddof, float mix_alpha, float neg_thresh,
                              float pos_thresh, float* out_adv, float* out_mean, float* out_std,
                              uint8_t* out_flags, hipStream_t stream);
 

@@ -78,15 +78,15 @@ def test_workspace_queries():
 def test_group_advantages_argument_errors():
     f = m.lib().mrl_group_advantages
     ok_tail = (FAKE, None, None, None, None)
-    assert f(None, FAKE, None, None, None, 8, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -1
-    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, None, None, None, None, None) == -1
-    assert f(FAKE, FAKE, None, None, None, 8, 0, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -2
-    assert f(FAKE, FAKE, None, None, None, -1, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -2
-    assert f(FAKE, FAKE, None, None, None, 8, 2, 5, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -7
-    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, -1.0, 0, 1.0, 0.2, 0.8, *ok_tail) == -7
-    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, 1e-6, 2, 1.0, 0.2, 0.8, *ok_tail) == -7
-    assert f(FAKE, FAKE, None, None, None, 8, 2, 1, 1e-6, 0, 1.5, 0.2, 0.8, *ok_tail) == -7
-    assert f(FAKE, FAKE, None, None, None, 0, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == 0
+    assert f(None, FAKE, None, None, None, None, 8, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -1
+    assert f(FAKE, FAKE, None, None, None, None, 8, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, None, None, None, None, None) == -1
+    assert f(FAKE, FAKE, None, None, None, None, 8, 0, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -2
+    assert f(FAKE, FAKE, None, None, None, None, -1, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -2
+    assert f(FAKE, FAKE, None, None, None, None, 8, 2, 5, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, None, 8, 2, 1, -1.0, 0, 1.0, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, None, 8, 2, 1, 1e-6, 2, 1.0, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, None, 8, 2, 1, 1e-6, 0, 1.5, 0.2, 0.8, *ok_tail) == -7
+    assert f(FAKE, FAKE, None, None, None, None, 0, 2, 1, 1e-6, 0, 1.0, 0.2, 0.8, *ok_tail) == 0
 
 
 def _loss(cfg, *, hidden=FAKE, ref=FAKE, B=4, T=8, G=2, d=128, V=100, dt=1, ws=FAKE, ws_bytes=1 << 30,

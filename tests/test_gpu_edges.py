@@ -186,6 +186,8 @@ def test_softmax_normalisation_via_lse(mrl, synth):
 ADV_CASES = [
     dict(mode=0), dict(mode=1), dict(mode=2), dict(mode=1, ddof=1), dict(mode=2, ddof=1),
     dict(mode=1, mix_alpha=0.0), dict(mode=0, mix_alpha=0.0), dict(mode=1, eps_norm=1e-3),
+    dict(mode=1, mix_alpha=0.2), dict(mode=0, mix_alpha=0.2), dict(mode=2, mix_alpha=0.5),
+    dict(mode=1, shift=True), dict(mode=0, mix_alpha=0.2, shift=True), dict(mode=2, shift=True, eps_norm=1e-3),
 ]
 
 
@@ -200,8 +202,12 @@ def test_group_advantages_modes(mrl, kw):
     sc = (rng.random(B) < 0.7).astype(np.uint8)
     own = (rng.random(B) < 0.5).astype(np.uint8)
     t = lambda a: torch.tensor(a, device="cuda")
+    kw, okw = dict(kw), dict(kw)
+    if kw.pop("shift", False):      # perturbed per-prompt baseline; the values are an input to both sides
+        del okw["shift"]
+        shift = (rng.normal(size=G) * 0.3).astype(np.float32)
+        kw["baseline_shift"], okw["baseline_shift"] = t(shift), shift.astype(np.float64)
     adv, mean, std, flags = mrl.group_advantages(t(r), t(gid), G, t(st), t(sc), t(own), **kw)
-    okw = dict(kw)
     a_o, m_o, s_o, f_o = orc.group_advantages(r.astype(np.float64), gid, G, st, sc, own, **okw)
     assert np.array_equal(flags.cpu().numpy(), f_o)
     assert np.allclose(mean.cpu().numpy(), m_o, rtol=1e-6, atol=1e-7)
@@ -219,7 +225,7 @@ def test_group_advantages_defaults_and_orphans(mrl):
     got = adv.cpu().numpy()
     assert np.allclose(got[:5], a_o, atol=1e-6) and got[4] == 0 and np.all(got[5:] == 0)
     assert np.allclose(mean.cpu().numpy(), m_o) and np.array_equal(flags.cpu().numpy(), f_o)
-    # XGRPO mix strictly between 0 and 1: both sides implement the same linear blend (rule unpinned by the paper)
+    # XGRPO mix strictly between 0 and 1 with orphans present
     own = torch.tensor([1, 1, 0, 0, 1, 1, 1], dtype=torch.uint8, device="cuda")
     adv2, *_ = mrl.group_advantages(r, gid, 3, None, own, own, mix_alpha=0.2)
     a2, *_ = orc.group_advantages(r.cpu().numpy()[:5].astype(np.float64), gid.cpu().numpy()[:5], 3, None,

@@ -148,7 +148,7 @@ def test_global_token_mean_and_batch_zn(mrl, synth):
     (2, 1, dict(), 2.0),                               # fp32 sanity path
 ])
 def test_response_level_ratio(mrl, synth, level, idx, over, jitter):
-    """Eq. (1) with the response-level ratio of App. G.1; responses span several 256-row passes."""
+    """Eq. (1) with the response-level ratio of App. I.1; responses span several 256-row passes."""
     sp = synth.spec(idx, **over)
     f32 = sp.dtype == torch.float32
     batch, got, want, st = _run_both(mrl, synth, sp, chunk_rows=0 if f32 else 256, ratio_level=level,

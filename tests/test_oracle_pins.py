@@ -167,7 +167,7 @@ def test_batch_zn_rescales_centred_advantages_to_unit_batch_variance():
 
 
 def test_unscored_members_enter_stats_but_get_zero_advantage():
-    # XGRPO (App. G.1): the peers' rewards only shift the baseline.
+    # XGRPO (App. I.1): the peers' rewards only shift the baseline.
     r = np.array([0, 0, 1, 0, 1, 1, 1, 0], dtype=np.float64)
     gid = np.zeros(8, dtype=int)
     own = np.array([1, 1, 1, 1, 0, 0, 0, 0], dtype=np.uint8)
@@ -179,6 +179,115 @@ def test_unscored_members_enter_stats_but_get_zero_advantage():
                                   is_own=own, eps_norm=0.0, mix_alpha=0.0)
     own_ref, *_ = orc.group_advantages(r[:4], gid[:4], 1, eps_norm=0.0)
     assert np.allclose(a0[:4], own_ref)
+
+
+# ---------------------------------------------------------------- mixing rule and perturbed baseline
+def _mixed_groups(seed, G=5, K=4, peers=6):
+    rng = np.random.default_rng(seed)
+    r, gid, own = [], [], []
+    for g in range(G):
+        r += list(rng.random(K + peers))
+        gid += [g] * (K + peers)
+        own += [1] * K + [0] * peers
+    perm = rng.permutation(len(r))
+    return (np.array(r)[perm], np.array(gid)[perm], np.array(own, dtype=np.uint8)[perm], G)
+
+
+@pytest.mark.parametrize("mode", [orc.ADV_CENTER, orc.ADV_GROUP_ZN])
+def test_mix_alpha_is_the_linear_blend_of_local_and_pooled_advantages(mode):
+    # Sec. 5.2: the local group-relative advantage is combined with its pool-aggregated
+    # counterpart; App. A gives the cross-model factor.  Endpoints against scipy's z-score
+    # on the own / pooled rewards, linearity in alpha in between, and the centred closed
+    # form r - ((1 - alpha) mean_own + alpha mean_pool).
+    import scipy.stats
+    r, gid, own, G = _mixed_groups(21)
+    ones = np.ones(r.size, np.uint8)
+    kw = dict(in_stats=ones, scored=own, is_own=own, mode=mode, eps_norm=0.0)
+    a0, *_ = orc.group_advantages(r, gid, G, mix_alpha=0.0, **kw)
+    a1, *_ = orc.group_advantages(r, gid, G, mix_alpha=1.0, **kw)
+    for g in range(G):
+        o = (gid == g) & (own == 1)
+        allm = gid == g
+        if mode == orc.ADV_GROUP_ZN:
+            assert np.allclose(a0[o], scipy.stats.zscore(r[o]), atol=1e-12)
+            assert np.allclose(a1[allm], np.where(own[allm] == 1, scipy.stats.zscore(r[allm]), 0.0), atol=1e-12)
+        else:
+            assert np.allclose(a0[o], r[o] - r[o].mean(), atol=1e-14)
+            assert np.allclose(a1[o], r[o] - r[allm].mean(), atol=1e-14)
+    for alpha in (0.2, 0.5, 0.85):
+        a, *_ = orc.group_advantages(r, gid, G, mix_alpha=alpha, **kw)
+        assert np.allclose(a - a0, alpha * (a1 - a0), atol=1e-13)
+        assert np.all(a[own == 0] == 0.0)
+        if mode == orc.ADV_CENTER:
+            for g in range(G):
+                o = (gid == g) & (own == 1)
+                base = (1 - alpha) * r[o].mean() + alpha * r[gid == g].mean()
+                assert np.allclose(a[o], r[o] - base, atol=1e-14)
+    # own advantages under the blend no longer sum to zero once the pool mean differs
+    a, *_ = orc.group_advantages(r, gid, G, mix_alpha=0.2, **kw)
+    assert max(abs(a[(gid == g) & (own == 1)].sum()) for g in range(G)) > 1e-3
+
+
+def test_baseline_shift_closed_form():
+    # App. C.4 control: a perturbation d_g of the per-prompt baseline moves every scored
+    # advantage of the group by -d_g (centred) or -d_g / (std_g + eps) (z-normalised); the
+    # reported statistics and the gate flags do not move.
+    r, gid, own, G = _mixed_groups(22)
+    ones = np.ones(r.size, np.uint8)
+    shift = np.array([0.3, -0.2, 0.0, 1.5, -0.05])
+    for alpha in (1.0, 0.2):
+        for mode, eps in ((orc.ADV_CENTER, 1e-6), (orc.ADV_GROUP_ZN, 1e-3)):
+            kw = dict(in_stats=ones, scored=own, is_own=own, mode=mode, eps_norm=eps, mix_alpha=alpha)
+            a, mean, std, fl = orc.group_advantages(r, gid, G, **kw)
+            b, mean2, std2, fl2 = orc.group_advantages(r, gid, G, baseline_shift=shift, **kw)
+            assert np.array_equal(mean, mean2) and np.array_equal(std, std2) and np.array_equal(fl, fl2)
+            for g in range(G):
+                o = (gid == g) & (own == 1)
+                if mode == orc.ADV_CENTER:
+                    want = -shift[g]
+                else:
+                    sd_o = np.std(r[o])
+                    want = -shift[g] * ((1 - alpha) / (sd_o + eps) + alpha / (std[g] + eps))
+                assert np.allclose(b[o] - a[o], want, atol=1e-12)
+            assert np.all(b[own == 0] == 0.0)
+    z, *_ = orc.group_advantages(r, gid, G, baseline_shift=np.zeros(G))
+    z0, *_ = orc.group_advantages(r, gid, G)
+    assert np.array_equal(z, z0)
+
+
+def test_prompt_level_baseline_leaves_expected_score_gradient_unchanged():
+    # Lemma "Prompt-level pooled baselines are unbiased" (App. I): for a softmax bandit
+    # with K = 2 rollouts per prompt, enumerate all arm pairs; the expectation of
+    # (1/K) sum_i A_i grad log pi(y_i), with centred advantages computed around a baseline
+    # moved by any constant, equals the one without the move (exact rationals would give
+    # equality; here to rounding).  grad log pi(a) = e_a - pi for softmax logits.
+    pi = np.array([0.5, 0.3, 0.2])
+    reward = np.array([1.0, 0.0, 0.0])
+    peers = np.array([1.0, 1.0, 0.0])           # fixed peer rewards entering the pooled mean
+
+    def expected_grad(shift):
+        g = np.zeros(3)
+        for y0, y1 in itertools.product(range(3), repeat=2):
+            r = np.concatenate([reward[[y0, y1]], peers])
+            own = np.array([1, 1, 0, 0, 0], np.uint8)
+            # the lemma needs a baseline that does not depend on the sampled responses:
+            # pooled statistics over the peers only (in_stats = not own)
+            a, *_ = orc.group_advantages(r, np.zeros(5, dtype=int), 1, in_stats=1 - own, scored=own,
+                                         is_own=own, mode=orc.ADV_CENTER,
+                                         baseline_shift=None if shift is None else np.array([shift]))
+            for yi, ai in ((y0, a[0]), (y1, a[1])):
+                score = -pi.copy()
+                score[yi] += 1.0
+                g += pi[y0] * pi[y1] * 0.5 * ai * score
+        return g
+
+    g0 = expected_grad(None)
+    assert np.linalg.norm(g0) > 0.1
+    # without any baseline the expectation is sum_y pi(y) r(y) (e_y - pi)
+    plain = sum(pi[y] * reward[y] * (np.eye(3)[y] - pi) for y in range(3))
+    assert np.allclose(g0, plain, atol=1e-14)
+    for shift in (0.7, -2.0):
+        assert np.allclose(expected_grad(shift), g0, atol=1e-14)
 
 
 # ---------------------------------------------------------------- P7 zero-support boundary
@@ -548,7 +657,7 @@ def test_entropy_closed_forms_and_library():
     assert np.all(ent <= np.log(13.0) + 1e-12)
 
 
-# ---------------------------------------------------------------- response-level ratio (App. G.1)
+# ---------------------------------------------------------------- response-level ratio (App. I.1)
 def _seq_tiny(seed, jitter=0.12):
     """Like _tiny, with jitters such that response-level ratios straddle the clip band."""
     t = _tiny(seed, B=6, T=4, G=3, V=9, d=4)
@@ -629,7 +738,7 @@ def test_response_ratio_special_cases():
         assert r["n_clipped_tokens"] == 0
         expect = -(wseq * t["adv"])[:, None] * m / (1.0 if level == 1 else np.maximum(m.sum(axis=1), 1)[:, None])
         assert np.allclose(r["g"].reshape(m.shape), expect, atol=1e-15)
-    # the clipped weight never exceeds 1 + eps in magnitude (App. G, proof of the PRP theorem)
+    # the clipped weight never exceeds 1 + eps in magnitude (App. I, proof of the PRP theorem)
     r = _run(t, cfg=dict(CFG, ratio_level=1))
     A = np.repeat(t["adv"], t["T"])
     live = t["m"].reshape(-1) & (np.abs(A) > 0)

@@ -58,7 +58,7 @@ def move_off_kinks(batch, oracle_logp, eps, margin=4e-3, shift=0.03):
 
 
 def move_off_kinks_seq(batch, oracle_logp, eps, level, margin=2e-2, shift=0.08):
-    """Response-level ratios (App. G.1): shifts the behaviour log-prob of the first scored token
+    """Response-level ratios (App. I.1): shifts the behaviour log-prob of the first scored token
     of every response whose ratio sits within `margin` (in log space) of a clip edge, so that fp32
     and fp64 take the same clip decision.  Uses the oracle's log-probs only."""
     B, T = batch["B"], batch["T"]
