@@ -34,6 +34,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
@@ -53,6 +54,9 @@ constexpr int LDS_BYTES = STASH_BYTES > PIPE_BYTES ? STASH_BYTES : PIPE_BYTES;
 constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
+#ifndef FWD_DIRECT
+#define FWD_DIRECT 1        // forward epilogue stores the logit stash from registers (0: staged through LDS)
+#endif
 
 // timing-probe switches (never defined in the library build)
 #ifdef PROBE_NODSREAD
@@ -180,6 +184,13 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // slot l%32 of row l/32 and fetches logical chunk slot ^ (h(k) << 1), the swizzle that makes
   // the transposing fragment reads below conflict-free.
   constexpr bool A_KMAJOR = (MODE == MODE_DW);
+  // FWD: the 16 rows of A fragment i are not 16 consecutive panel rows but
+  //   rho(i, r) = 32*(i/2) + 8*(r/4) + 4*(i%2) + r%4      (within the wave's 128 rows),
+  // so that a lane's accumulators (i = 2t, 2t+1; e = 0..3) are 8 consecutive vocabulary ids
+  // and the fp16 stash can be stored from registers, 16 bytes per lane, without an LDS round
+  // trip.  The chunk swizzle of the A panel then takes row bits 1, 3, 4 (the ones that vary
+  // inside a fragment) instead of bits 1-3.
+  constexpr bool A_PERM = (MODE == MODE_FWD) && FWD_DIRECT;
   const int64_t a_kstep = A_KMAJOR ? (int64_t)BK * p.lda : BK;   // elements per K panel
   const int lrow = lane >> 3;
   const uint16_t* a_ptr[8];
@@ -188,6 +199,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   for (int i = 0; i < 8; ++i) {
     const int r = (wave * 8 + i) * 8 + lrow;          // row within the 256-row panel
     const int lchunk = (lane & 7) ^ ((r >> 1) & 7);
+    const int lchunk_a = A_PERM ? ((lane & 7) ^ (((r >> 1) & 1) | (((r >> 3) & 3) << 1))) : lchunk;
     int ra = m0 + r; ra = ra < M ? ra : M - 1;
     int rb = n0 + r; rb = rb < N ? rb : N - 1;
     int64_t rowa = ra, rowb = rb;
@@ -196,7 +208,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       const int k = 2 * (wave * 8 + i) + (lane >> 5);  // k row within the panel
       a_ptr[i] = p.A + (int64_t)k * p.lda + m0 + (((lane & 31) ^ (kswz(k) << 1)) << 3);
     } else {
-      a_ptr[i] = p.A + rowa * p.lda + lchunk * 8;
+      a_ptr[i] = p.A + rowa * p.lda + lchunk_a * 8;
     }
     b_ptr[i] = p.B + rowb * p.ldb + lchunk * 8;
   }
@@ -264,7 +276,12 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) {
     const int chunk = ((ks << 2) | fq) ^ ((frow >> 1) & 7);
-    a_off[ks] = (wm * 128 + frow) * 128 + (chunk << 4);
+    if (A_PERM) {
+      const int chunk_a = ((ks << 2) | fq) ^ (((frow >> 1) & 1) | ((frow >> 2) << 1));
+      a_off[ks] = (wm * 128 + 8 * (frow >> 2) + (frow & 3)) * 128 + (chunk_a << 4);
+    } else {
+      a_off[ks] = (wm * 128 + frow) * 128 + (chunk << 4);
+    }
     b_off[ks] = TILE_BYTES + (wn * 128 + frow) * 128 + (chunk << 4);
   }
 
@@ -292,7 +309,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(q + 2048));
       return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
-    return *reinterpret_cast<const bf16x8*>(smem + st + a_off[ks] + ib * 2048);
+    return *reinterpret_cast<const bf16x8*>(smem + st + a_off[ks] +
+                                            (A_PERM ? (ib >> 1) * 4096 + (ib & 1) * 512 : ib * 2048));
   };
 
   f32x4 acc[8][8];
@@ -317,9 +335,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // were issued in groups 4-7 of panel kt-1); groups 4-6 then read the next B set and groups 4-7
   // issue the direct loads of panel kt+2 into the released slot, each in the shadow of a group's
   // MFMAs.
-  // The loop body (two panels, so that the B sets have fixed registers) is branch-free; the last
-  // one or two panels are peeled, and loads that would run past the end re-fetch the last panel
-  // into a slot nobody reads.
+  // The loop body (two panels, so that the B sets have fixed registers) is branch-free; loads
+  // that would run past the end re-fetch the last panel into a slot nobody reads.
   bf16x8 fbx[2][2][8];   // [set][K step][16-column block]
   bf16x8 fax[4][2];      // [ring slot][K step]
   auto read_b = [&](int st, int ks, int j) -> bf16x8 {
@@ -404,7 +421,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // ---- epilogues.  Accumulator element (i, j, e) of this lane is
   //   row m = m0 + wm*128 + i*16 + 4*(lane>>4) + e
   //   col n = n0 + wn*128 + j*16 + (lane & 15)
-  __syncthreads();
+  if (!A_PERM) __syncthreads();   // the staged epilogues reuse the panels' LDS
   const int mrow_base = m0 + wm * 128 + 4 * fq;
   const int ncol_base = n0 + wn * 128 + frow;
 
@@ -413,6 +430,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     constexpr float LOG2E = 1.4426950408889634f;
     const bool full = (m0 + BM <= p.V);
     const int pidx = tm * 2 + wm;
+    // vocabulary id of accumulator (i, e) of this lane
+    auto vrow = [&](int i, int e) {
+      return A_PERM ? m0 + wm * 128 + 32 * (i >> 1) + 8 * fq + 4 * (i & 1) + e : mrow_base + i * 16 + e;
+    };
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int n = ncol_base + j * 16;
@@ -426,7 +447,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) mx = (mrow_base + i * 16 + e) < p.V ? fmaxf(mx, acc[i][j][e]) : mx;
+          for (int e = 0; e < 4; ++e) mx = vrow(i, e) < p.V ? fmaxf(mx, acc[i][j][e]) : mx;
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -443,7 +464,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float t = exp2_fast(fmaf(acc[i][j][e], LOG2E, mneg));
-            s += (mrow_base + i * 16 + e) < p.V ? t : 0.f;
+            s += vrow(i, e) < p.V ? t : 0.f;
           }
       }
       s += __shfl_xor(s, 16);
@@ -461,13 +482,29 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
           for (int e = 0; e < 4; ++e) {
             const float z = acc[i][j][e];
             const float w = exp2_fast(fmaf(z, LOG2E, mneg));
-            t += (full || (mrow_base + i * 16 + e) < p.V) ? w * z : 0.f;
+            t += (full || vrow(i, e) < p.V) ? w * z : 0.f;
           }
         t += __shfl_xor(t, 16);
         t += __shfl_xor(t, 32);
         if (fq == 0 && n < N) p.part_ez[(int64_t)pidx * p.part_stride + n] = t;
       }
-      if (p.zstash != nullptr) {
+      if (A_PERM) {
+        // logits as fp16 straight from the accumulators: 8 consecutive vocabulary ids per lane
+        // and store, the four lanes of a token row side by side (64 bytes)
+        if (p.zstash != nullptr && n < N) {
+          uint16_t* zrow = p.zstash + (int64_t)n * p.ldz + m0 + wm * 128 + 8 * fq;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            f16x8 h;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              h[e] = (_Float16)__builtin_amdgcn_fmed3f(acc[2 * t][j][e], -65504.f, 65504.f);
+              h[4 + e] = (_Float16)__builtin_amdgcn_fmed3f(acc[2 * t + 1][j][e], -65504.f, 65504.f);
+            }
+            *reinterpret_cast<f16x8*>(zrow + 32 * t) = h;
+          }
+        }
+      } else if (p.zstash != nullptr) {
         // stage the logits as fp16 in LDS, [token][vocab], for coalesced row stores below
         unsigned char* srow = smem + (wn * 128 + j * 16 + frow) * (STASH_LD * 2) + (wm * 128 + 4 * fq) * 2;
 #pragma unroll
@@ -480,7 +517,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         }
       }
     }
-    if (p.zstash != nullptr) {
+    if (!A_PERM && p.zstash != nullptr) {
       __syncthreads();
       // 32 lanes store one 512-byte row segment; a wave instruction covers two token rows
 #pragma unroll 4
