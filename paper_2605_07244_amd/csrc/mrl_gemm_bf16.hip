@@ -604,12 +604,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 
 template <int MODE>
 void launch(const Params& p, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_bf16<MODE>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    attr_set = true;
-  }
+  static LdsLimit lds_limit;
+  lds_limit.ensure(reinterpret_cast<const void*>(&gemm_nt_bf16<MODE>), LDS_BYTES);
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
   const int blocks = num_blocks(Mt, Nt);
   hipLaunchKernelGGL(gemm_nt_bf16<MODE>, dim3(blocks), dim3(NTHREADS), LDS_BYTES, stream, p);

@@ -4,12 +4,28 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace mrl {
 
 // Column padding of the per-chunk logit / dz buffers: the vocabulary is padded
 // to a multiple of the GEMM tile so that inner kernels never see a ragged K.
 constexpr int kTile = 256;
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// A kernel that asks for more than 64 KB of dynamic LDS needs its limit raised first; the
+// attribute belongs to the (kernel, device) pair, so it is set once on every device used.
+struct LdsLimit {
+  std::atomic<bool> done[64] = {};
+  void ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && done[dev].load(std::memory_order_acquire)) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (tracked) done[dev].store(true, std::memory_order_release);
+  }
+};
 
 // Number of (max, sum-exp) partials each token row receives from the forward
 // kernel: the bf16 kernel emits two per 256-wide vocabulary tile (one per wave

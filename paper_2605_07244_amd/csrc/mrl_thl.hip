@@ -145,12 +145,8 @@ extern "C" int mrl_thl_word_align(const float* src_logp, const uint8_t* src_mask
   if (rc != MRL_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t lds = (size_t)max_words * 12;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_thl_word_align),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, THL_MAX_WORDS * 12);
-    attr_set = true;
-  }
+  static LdsLimit lds_limit;
+  lds_limit.ensure(reinterpret_cast<const void*>(&k_thl_word_align), THL_MAX_WORDS * 12);
   if (out_bad_words) hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(1), 0, s, reinterpret_cast<unsigned long long*>(out_bad_words));
   hipLaunchKernelGGL(k_thl_word_align, dim3((unsigned)B), dim3(THL_THREADS), lds, s, src_logp, src_mask,
                      src_word_map, src_map_len, tgt_mask, tgt_word_map, tgt_map_len, S_src, S_tgt, max_words,
