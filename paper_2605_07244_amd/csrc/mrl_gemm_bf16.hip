@@ -21,7 +21,9 @@
 //   FWD: A = W (vocabulary rows), B = H (token rows, gathered).  The MFMA result
 //        layout keeps 4 rows x 1 column per lane, so putting the vocabulary on
 //        the M side makes the max / sum-exp reduction over the vocabulary an
-//        in-register reduction with two cross-lane steps.
+//        in-register reduction with two cross-lane steps.  The fragment rows are
+//        permuted so that a lane's accumulators are 8 consecutive vocabulary ids
+//        and the fp16 logit stash is stored straight from registers.
 //   DH : A = dz rows (tokens), B = W^T;  rows are scattered to the padded slots.
 //   DW : A = dz^T, read from the dz rows themselves (K-major panel, transposing LDS
 //        reads), B = H^T; fp32 read-modify-write of dW.
@@ -33,7 +35,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
@@ -54,9 +55,6 @@ constexpr int LDS_BYTES = STASH_BYTES > PIPE_BYTES ? STASH_BYTES : PIPE_BYTES;
 constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
-#ifndef FWD_DIRECT
-#define FWD_DIRECT 1        // forward epilogue stores the logit stash from registers (0: staged through LDS)
-#endif
 
 // timing-probe switches (never defined in the library build)
 #ifdef PROBE_NODSREAD
@@ -190,7 +188,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // and the fp16 stash can be stored from registers, 16 bytes per lane, without an LDS round
   // trip.  The chunk swizzle of the A panel then takes row bits 1, 3, 4 (the ones that vary
   // inside a fragment) instead of bits 1-3.
-  constexpr bool A_PERM = (MODE == MODE_FWD) && FWD_DIRECT;
+  constexpr bool A_PERM = (MODE == MODE_FWD);
   const int64_t a_kstep = A_KMAJOR ? (int64_t)BK * p.lda : BK;   // elements per K panel
   const int lrow = lane >> 3;
   const uint16_t* a_ptr[8];
@@ -424,9 +422,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   if (blockIdx.x == 8 && threadIdx.x == 0) { g_probe_clk[0] = clock64() - c0; g_probe_clk[1] = wall_clock64() - w0; }
 #endif
   // ---- epilogues.  Accumulator element (i, j, e) of this lane is
-  //   row m = m0 + wm*128 + i*16 + 4*(lane>>4) + e
+  //   row m = m0 + wm*128 + i*16 + 4*(lane>>4) + e      (FWD: the permuted row, see vrow below)
   //   col n = n0 + wn*128 + j*16 + (lane & 15)
-  if (!A_PERM) __syncthreads();   // the staged epilogues reuse the panels' LDS
+  if (MODE == MODE_DH) __syncthreads();   // its staged epilogue reuses the panels' LDS
   const int mrow_base = m0 + wm * 128 + 4 * fq;
   const int ncol_base = n0 + wn * 128 + frow;
 
@@ -437,7 +435,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     const int pidx = tm * 2 + wm;
     // vocabulary id of accumulator (i, e) of this lane
     auto vrow = [&](int i, int e) {
-      return A_PERM ? m0 + wm * 128 + 32 * (i >> 1) + 8 * fq + 4 * (i & 1) + e : mrow_base + i * 16 + e;
+      return m0 + wm * 128 + 32 * (i >> 1) + 8 * fq + 4 * (i & 1) + e;
     };
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -493,7 +491,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         t += __shfl_xor(t, 32);
         if (fq == 0 && n < N) p.part_ez[(int64_t)pidx * p.part_stride + n] = t;
       }
-      if (A_PERM) {
+      {
         // logits as fp16 straight from the accumulators: 8 consecutive vocabulary ids per lane
         // and store, the four lanes of a token row side by side (64 bytes)
         if (p.zstash != nullptr && n < N) {
@@ -506,32 +504,14 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
               h[e] = (_Float16)__builtin_amdgcn_fmed3f(acc[2 * t][j][e], -65504.f, 65504.f);
               h[4 + e] = (_Float16)__builtin_amdgcn_fmed3f(acc[2 * t + 1][j][e], -65504.f, 65504.f);
             }
-            *reinterpret_cast<f16x8*>(zrow + 32 * t) = h;
+            // streaming store (non-temporal, device scope): the stash is 5 GB per launch and is
+            // next read by the conversion pass, so it should not displace operand panels from the
+            // L2 and the memory-side cache (2 % of the launch against a plain store)
+            // The store is written in assembly for its cache policy bits; the two wait states
+            // after it are the ones the hardware needs before the data registers of a store wider
+            // than 8 bytes may be overwritten (the compiler inserts them for its own stores only).
+            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" :: "v"(zrow + 32 * t), "v"(h) : "memory");
           }
-        }
-      } else if (p.zstash != nullptr) {
-        // stage the logits as fp16 in LDS, [token][vocab], for coalesced row stores below
-        unsigned char* srow = smem + (wn * 128 + j * 16 + frow) * (STASH_LD * 2) + (wm * 128 + 4 * fq) * 2;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          f16x4 h;
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            h[e] = (_Float16)__builtin_amdgcn_fmed3f(acc[i][j][e], -65504.f, 65504.f);
-          *reinterpret_cast<f16x4*>(srow + i * 32) = h;
-        }
-      }
-    }
-    if (!A_PERM && p.zstash != nullptr) {
-      __syncthreads();
-      // 32 lanes store one 512-byte row segment; a wave instruction covers two token rows
-#pragma unroll 4
-      for (int k = 0; k < 32; ++k) {
-        const int c = tid + NTHREADS * k;
-        const int row = c >> 5, col = c & 31;
-        if (n0 + row < N) {
-          const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * (STASH_LD * 2) + col * 16);
-          *reinterpret_cast<u32x4*>(p.zstash + (int64_t)(n0 + row) * p.ldz + m0 + col * 8) = v;
         }
       }
     }
