@@ -290,6 +290,47 @@ def test_prompt_level_baseline_leaves_expected_score_gradient_unchanged():
         assert np.allclose(expected_grad(shift), g0, atol=1e-14)
 
 
+def test_pooled_baseline_variance_identity():
+    # Thm. "When pooled XGRPO normalization reduces variance" (App. I): for baselines that do not
+    # depend on the scored rollout, Var((r - b_pool) s) - Var((r - b_n) s) = H (Delta^2 - 2 D Delta)
+    # with H = E|s|^2, b* = E[r |s|^2] / H, D = b_n - b*, Delta = b_n - b_pool.  The advantages come
+    # from the oracle (one own rollout per group, the baseline formed by fixed other entries); the
+    # expectation over the own rollout is an exact enumeration of a softmax bandit.
+    pi = np.array([0.55, 0.25, 0.15, 0.05])
+    reward = np.array([1.0, 0.0, 1.0, 0.0])
+    score = np.eye(4) - pi                                  # grad log pi(a) = e_a - pi
+    sq = np.sum(score ** 2, axis=1)
+    H = float(pi @ sq)
+    b_star = float(pi @ (reward * sq)) / H
+    local = np.array([1.0, 0.0, 0.0, 1.0, 0.0])              # the learner's other rollouts: b_n = 0.4
+    peers = np.array([1.0, 1.0, 1.0, 0.0, 1.0, 1.0, 0.0])    # the other policies' rollouts
+
+    def variance(stat_rewards):
+        # own rollout y (scored, not in the statistics) + the fixed entries that form the baseline
+        first = np.zeros(4)
+        second = 0.0
+        for y in range(4):
+            r = np.concatenate([[reward[y]], stat_rewards])
+            scored = np.zeros(r.size, np.uint8); scored[0] = 1
+            a, mean, _, _ = orc.group_advantages(r, np.zeros(r.size, dtype=int), 1, in_stats=1 - scored,
+                                                 scored=scored, mode=orc.ADV_CENTER)
+            assert abs(mean[0] - stat_rewards.mean()) < 1e-15
+            first += pi[y] * a[0] * score[y]
+            second += pi[y] * a[0] ** 2 * sq[y]
+        return second - float(first @ first), first
+
+    var_n, g_n = variance(local)
+    var_pool, g_pool = variance(np.concatenate([local, peers]))
+    assert np.allclose(g_n, g_pool, atol=1e-15)               # same expected direction (the lemma)
+    b_n, b_pool = local.mean(), np.concatenate([local, peers]).mean()
+    D, Delta = b_n - b_star, b_n - b_pool
+    assert abs(Delta) > 0.1
+    assert abs((var_pool - var_n) - H * (Delta ** 2 - 2 * D * Delta)) < 1e-14
+    # and the completed square: Var(b) = Var(b*) + H (b - b*)^2
+    var_star, _ = variance(np.array([b_star]))
+    assert abs(var_n - (var_star + H * D ** 2)) < 1e-14
+
+
 # ---------------------------------------------------------------- P7 zero-support boundary
 def test_zero_support_boundary_sign():
     # Prop. "Zero-support success boundary": learner all-fail, pool holds a
