@@ -185,3 +185,55 @@ def test_source_without_any_word_leaves_the_row_inactive():
     out = thl.word_align_logprobs(lp, np.array([[0, 0]]), np.array([[0, 1]]), [2],
                                   np.array([[1, 1]]), np.array([[0, 1]]), [2], IGN)
     assert np.all(out == IGN)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_aligned_denominator_ratio_envelope(seed):
+    """Cor. "Importance-ratio envelope induced by THL" (App. I): the response-level ratio taken
+    against the aligned trace is rho * exp(R) with R = L_mu - L~_mu, the source log-prob mass of
+    words without target tokens and of tokens without a word; exact refinement gives R = 0.
+    Ties the alignment oracle to the loss oracle: the aligned trace goes in as behaviour log-probs
+    of the target grid (positions left at ignore_value are masked out) and rho~ is read off the
+    surrogate of a single response with a unit advantage and an inactive clip."""
+    from oracle import mrl_oracle as orc
+    src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len = _random_case(40 + seed, B=6, truncate=False)
+    aligned = thl.word_align_logprobs(src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len, IGN)
+    rng = np.random.default_rng(seed)
+    cfg = dict(orc.default_config(), clip_eps_low=1.0, clip_eps_high=1e30, kl_beta=0.0, ratio_level=1)
+    checked = 0
+    for i in range(src_lp.shape[0]):
+        s_idx, s_w = _valid_tokens(src_m[i], src_map[i], src_len[i])
+        t_idx, t_w = _valid_tokens(tgt_m[i], tgt_map[i], tgt_len[i])
+        tok_mask = (tgt_m[i] == 1) & (aligned[i] != IGN)
+        if not tok_mask.any():
+            continue
+        T = tgt_m.shape[1]
+        logp = -rng.gamma(1.0, 0.3, size=T)                 # the learner's log-probs on the target grid
+        out = orc.loss_from_logp(logp, tok_mask[None, :], aligned[i], None, np.array([1.0]), np.array([0]),
+                                 None, 1, T, 1, cfg)
+        rho_tilde = -out["loss_pg"]                          # one response, A = 1, c sums to 1
+        L_theta = logp[tok_mask].sum()
+        # ideal ratio: the whole source trace as denominator
+        L_mu = src_lp[i, s_idx].sum()
+        rho = np.exp(L_theta - L_mu)
+        # residual by its definition: words nobody receives on the target side, tokens without a word
+        tgt_words = set(int(w) for w in t_w if w != thl.NONE)
+        R = sum(src_lp[i, s_idx[p]] for p in range(len(s_idx))
+                if s_w[p] == thl.NONE or int(s_w[p]) not in tgt_words)
+        assert abs(np.log(rho_tilde) - (np.log(rho) + R)) < 1e-10
+        n_mis = sum(1 for p in range(len(s_idx)) if s_w[p] == thl.NONE or int(s_w[p]) not in tgt_words)
+        bound = np.max(np.abs(src_lp[i, s_idx])) if len(s_idx) else 0.0
+        assert abs(R) <= bound * n_mis + 1e-12
+        assert np.exp(-abs(R)) * rho * (1 - 1e-12) <= rho_tilde <= np.exp(abs(R)) * rho * (1 + 1e-12)
+        checked += 1
+    assert checked >= 3
+    # exact refinement: same words on both sides, nothing unmapped => rho~ = rho
+    src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len = _random_case(50 + seed, B=4, p_none=0.0,
+                                                                            drop_words=False, truncate=False)
+    aligned = thl.word_align_logprobs(src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len, IGN)
+    for i in range(4):
+        s_idx, s_w = _valid_tokens(src_m[i], src_map[i], src_len[i])
+        tok_mask = (tgt_m[i] == 1) & (aligned[i] != IGN)
+        if not tok_mask.any() or np.any(s_w == thl.NONE):
+            continue
+        assert abs(aligned[i][tok_mask].sum() - src_lp[i, s_idx].sum()) < 1e-10
