@@ -130,3 +130,107 @@ def test_reproducible_and_argument_errors(mrl, synth):
         _gpu(mrl, b, max_words=8193)
     with pytest.raises(mrl.MrlError):
         _gpu(mrl, b, max_words=0)
+
+
+@pytest.mark.parametrize("ratio_level", [0, 1])
+def test_prp_step_with_aligned_peer_denominator(mrl, synth, ratio_level):
+    """Regime 1 end to end through the C ABI (Sec. 5.1, THL-aligned peer denominator): a peer's
+    trace on its own token grid is aligned onto the learner's grid by mrl_thl_word_align, the
+    positions it leaves at ignore_value are masked out, and the aligned trace is the behaviour
+    log-prob of mrl_grpo_loss_fwd_bwd (token ratio of Eq. 1, or the response-level ratio of
+    App. I.1).  The same chain runs on the two CPU oracles; log-probs, loss and gradients compare
+    to the usual tolerances, masks bit-exactly."""
+    from oracle import mrl_oracle as orc
+    from tests import util
+    B, G, S_src, T, V, d = 12, 3, 80, 96, 1000, 128
+    # token ratios: the full mix of mismatches (a word without source mass gets an aligned value of 0
+    # and a clipped ratio); response ratios: equal word sets on both sides, or a single such word
+    # would put the whole response far outside the clip band
+    mism = dict(p_none=0.05, p_drop_word=0.05, p_drift=0.2) if ratio_level == 0 else \
+        dict(p_none=0.0, p_drop_word=0.0, p_drift=0.0)
+    b = synth.make_thl(B, S_src, T, seed=4242, prompt_max=16, **mism)
+    g = torch.Generator("cuda").manual_seed(99)
+    H = torch.randn(B * T, d, device="cuda", generator=g).to(torch.bfloat16)
+    W = (0.05 * torch.randn(V, d, device="cuda", generator=g)).to(torch.bfloat16)
+    targets = torch.randint(0, V, (B * T,), device="cuda", generator=g, dtype=torch.int32)
+    # the learner's own log-probs (from the CPU oracle) centre the synthetic peer trace
+    lp_o, _ = orc.token_logprobs(util.to_f64(H), util.to_f64(W), targets.cpu().numpy())
+    proxy = lp_o.reshape(B, T)
+    # source trace: per word, the learner-side mass of the word plus a little noise, split evenly
+    # over the word's source tokens (so that ratios are of order one); None tokens get any value
+    rng = np.random.default_rng(7)
+    c = {k: (v.cpu().numpy() if isinstance(v, torch.Tensor) else v) for k, v in b.items()}
+    src_lp = -rng.gamma(1.0, 1.0, size=(B, S_src))
+    noise = 0.15 if ratio_level == 0 else 0.03
+    for i in range(B):
+        t_idx = np.nonzero(c["tgt_mask"][i])[0][: int(c["tgt_map_len"][i])]
+        s_idx = np.nonzero(c["src_mask"][i])[0][: int(c["src_map_len"][i])]
+        tot, cnt = {}, {}
+        for p, pos in enumerate(t_idx):
+            w = int(c["tgt_word_map"][i][p])
+            if w >= 0:
+                tot[w] = tot.get(w, 0.0) + proxy[i, pos]
+        for p in range(len(s_idx)):
+            w = int(c["src_word_map"][i][p])
+            if w >= 0:
+                cnt[w] = cnt.get(w, 0) + 1
+        jit = {w: rng.normal() * noise for w in cnt}
+        for p, pos in enumerate(s_idx):
+            w = int(c["src_word_map"][i][p])
+            if w >= 0 and w in tot:
+                src_lp[i, pos] = (tot[w] + jit[w]) / cnt[w]
+    b["src_logp"] = torch.tensor(src_lp, dtype=torch.float32, device="cuda")
+
+    aligned, bad = mrl.thl_word_align(b["src_logp"], b["src_mask"], b["src_word_map"], b["src_map_len"],
+                                      b["tgt_mask"], b["tgt_word_map"], b["tgt_map_len"], b["max_words"], IGN)
+    assert int(bad.item()) == 0
+    aligned_o = _oracle(b)
+    mask_g = (b["tgt_mask"].bool() & (aligned != IGN))
+    mask_o = (c["tgt_mask"] == 1) & (aligned_o != IGN)
+    assert np.array_equal(mask_g.cpu().numpy(), mask_o)
+
+    rewards = torch.tensor((rng.random(B) < 0.4).astype(np.float32), device="cuda")
+    gid = torch.arange(B, device="cuda", dtype=torch.int32) % G
+    adv, _, _, _ = mrl.group_advantages(rewards, gid, G)
+    adv_o, _, _, _ = orc.group_advantages(rewards.cpu().numpy().astype(np.float64), gid.cpu().numpy(), G)
+    assert np.allclose(adv.cpu().numpy(), adv_o, rtol=2e-6, atol=1e-7)
+    ref = torch.tensor(proxy.reshape(-1) + 0.1 * rng.normal(size=B * T), dtype=torch.float32, device="cuda")
+    eps = 0.2
+    cfg = dict(clip_eps_low=eps, clip_eps_high=eps, kl_beta=0.04, sgt_lambda=0.1, loss_agg=0, ratio_level=ratio_level)
+
+    # clip decisions sit on the oracle's side of the kinks by a margin: tokens (or, for the response
+    # ratio, responses) closer than that are taken out of the mask on both sides
+    delta = np.where(mask_o, lp_o.reshape(B, T) - aligned_o, 0.0)
+    if ratio_level == 0:
+        near = np.zeros_like(mask_o)
+        for edge in (np.log1p(-eps), np.log1p(eps)):
+            near |= mask_o & (np.abs(delta - edge) < 4e-3)
+        mask_o = mask_o & ~near
+    else:
+        expo = delta.sum(axis=1)
+        for edge in (np.log1p(-eps), np.log1p(eps)):
+            mask_o[np.abs(expo - edge) < 2e-2] = False
+    mask_t = torch.tensor(mask_o.astype(np.uint8), device="cuda")
+    behav = torch.where(mask_t.bool(), aligned, torch.zeros_like(aligned)).reshape(-1).contiguous()
+
+    seq_kind = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    lc = mrl.LossConfig(clip_eps_low=eps, clip_eps_high=eps, kl_beta=0.04, sgt_lambda=0.1, chunk_rows=256,
+                        ratio_level=ratio_level, dh_dtype=mrl.BF16)
+    got = mrl.grpo_loss_fwd_bwd(H, W, targets, mask_t.reshape(-1), behav, ref, adv, gid, seq_kind, B, T, G, lc)
+    torch.cuda.synchronize()
+    st = mrl.read_stats(got["stats"])
+    want = orc.grpo_loss_fwd_bwd(util.to_f64(H), util.to_f64(W), targets.cpu().numpy(), mask_o,
+                                 np.where(mask_o, aligned_o, 0.0).reshape(-1), util.to_f64(ref),
+                                 adv.cpu().numpy().astype(np.float64), gid.cpu().numpy(), seq_kind.cpu().numpy(),
+                                 B, T, G, cfg)
+    m = mask_o.reshape(-1)
+    assert m.sum() > 200
+    assert np.max(np.abs(got["logp"].cpu().numpy()[m] - want["logp"][m])) <= util.LOGP_TOL
+    assert st["n_scored_tokens"] == want["n_scored_tokens"]
+    assert st["n_clipped_tokens"] == want["n_clipped_tokens"]
+    assert 0 < want["n_clipped_tokens"] < want["n_scored_tokens"]        # both branches of the clip are exercised
+    pg_abs = float(np.sum(want["c"] * np.abs(np.minimum(want["s1"], want["s2"]))))
+    assert abs(st["loss_pg"] - want["loss_pg"]) <= util.REL_TOL * pg_abs
+    assert abs(st["loss_kl"] - want["loss_kl"]) <= util.REL_TOL * abs(want["loss_kl"])
+    assert util.rel_fro(util.to_f64(got["dH"]), want["dH"]) <= util.REL_TOL
+    assert util.rel_fro(util.to_f64(got["dW"]), want["dW"]) <= util.REL_TOL
