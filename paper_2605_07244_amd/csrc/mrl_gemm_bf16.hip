@@ -193,17 +193,26 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int lrow = lane >> 3;
   const uint16_t* a_ptr[8];
   const uint16_t* b_ptr[8];
+  // Workgroups that share a panel (same sm for A, same sn for B) walk its row blocks in a
+  // different cyclic order, so that they do not all ask the L2 for the same lines at the same
+  // moment (1-2 % on the forward and dH launches).
+  const int rot_a = (2 * sn) & 7, rot_b = sm & 7;
+  uint32_t lds_a[8], lds_b[8];                        // LDS offset of load i within the wave's 8 KB
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int r = (wave * 8 + i) * 8 + lrow;          // row within the 256-row panel
-    const int lchunk = (lane & 7) ^ ((r >> 1) & 7);
-    const int lchunk_a = A_PERM ? ((lane & 7) ^ (((r >> 1) & 1) | (((r >> 3) & 3) << 1))) : lchunk;
+    const int ia = (i + rot_a) & 7, ib = (i + rot_b) & 7;
+    lds_a[i] = __builtin_amdgcn_readfirstlane(ia * 1024);
+    lds_b[i] = __builtin_amdgcn_readfirstlane(ib * 1024);
+    const int r = (wave * 8 + ia) * 8 + lrow;         // row within the 256-row panel
+    const int rB = (wave * 8 + ib) * 8 + lrow;
+    const int lchunk = (lane & 7) ^ ((rB >> 1) & 7);
+    const int lchunk_a = A_PERM ? ((lane & 7) ^ (((r >> 1) & 1) | (((r >> 3) & 3) << 1))) : ((lane & 7) ^ ((r >> 1) & 7));
     int ra = m0 + r; ra = ra < M ? ra : M - 1;
-    int rb = n0 + r; rb = rb < N ? rb : N - 1;
+    int rb = n0 + rB; rb = rb < N ? rb : N - 1;
     int64_t rowa = ra, rowb = rb;
     if (MODE == MODE_FWD) rowb = p.row_index[rb];
     if (A_KMAJOR) {
-      const int k = 2 * (wave * 8 + i) + (lane >> 5);  // k row within the panel
+      const int k = 2 * (wave * 8 + ia) + (lane >> 5);  // k row within the panel
       a_ptr[i] = p.A + (int64_t)k * p.lda + m0 + (((lane & 31) ^ (kswz(k) << 1)) << 3);
     } else {
       a_ptr[i] = p.A + rowa * p.lda + lchunk_a * 8;
@@ -228,8 +237,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     const int koff = kt * BK;
 #pragma unroll
     for (int i = i0; i < i0 + n; ++i) {
-      load_lds16(a_ptr[i] + kt * a_kstep, st + i * 1024);
-      load_lds16(b_ptr[i] + koff, st + TILE_BYTES + i * 1024);
+      load_lds16(a_ptr[i] + kt * a_kstep, st + lds_a[i]);
+      load_lds16(b_ptr[i] + koff, st + TILE_BYTES + lds_b[i]);
     }
   };
 
@@ -348,9 +357,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   auto issue_range = [&](int kt, int slot, int j0, int j1) {
 #pragma unroll
     for (int j = j0; j < j1; ++j) {
-      const uint32_t st = slot * STAGE_BYTES + wave_lds + (j >> 1) * 1024;
-      if (j & 1) load_lds16(b_ptr[j >> 1] + kt * BK, st + TILE_BYTES);
-      else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st);
+      const uint32_t st = slot * STAGE_BYTES + wave_lds;
+      if (j & 1) load_lds16(b_ptr[j >> 1] + kt * BK, st + TILE_BYTES + lds_b[j >> 1]);
+      else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st + lds_a[j >> 1]);
     }
   };
   auto panel = [&](int set, int st_cur, int st_nxt, int kt_load, int slot_load, int kt_pre) {
