@@ -196,7 +196,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // Workgroups that share a panel (same sm for A, same sn for B) walk its row blocks in a
   // different cyclic order, so that they do not all ask the L2 for the same lines at the same
   // moment (1-2 % on the forward and dH launches).
-  const int rot_a = (2 * sn) & 7, rot_b = sm & 7;
+  const int rot_a = (sn * (8 / SUP_N)) & 7, rot_b = (sm * (8 / SUP_M)) & 7;
   uint32_t lds_a[8], lds_b[8];                        // LDS offset of load i within the wave's 8 KB
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
