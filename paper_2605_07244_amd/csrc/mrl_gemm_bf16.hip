@@ -39,9 +39,6 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
-#ifndef PF_DIST
-#define PF_DIST 0           // L2 prefetch distance in K panels (0 = off, the setting for real data: see below)
-#endif
 constexpr int NSTAGE = 2;                          // LDS double buffer of K panels
 constexpr int TILE_BYTES = BM * BK * 2;            // one operand panel: 32 KB (256 rows x 128 B)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
@@ -55,28 +52,6 @@ constexpr int LDS_BYTES = STASH_BYTES > PIPE_BYTES ? STASH_BYTES : PIPE_BYTES;
 constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
-
-// timing-probe switches (never defined in the library build)
-#ifdef PROBE_NODSREAD
-#define PROBE_RD(x)
-#else
-#define PROBE_RD(x) x
-#endif
-#ifdef PROBE_NOGLOAD
-#define PROBE_LD(x)
-#else
-#define PROBE_LD(x) x
-#endif
-#if PF_DIST > 0 && !defined(PROBE_NOGLOAD)
-#define PF_PENDING 1        // direct loads allowed in flight at the barrier: the panel's prefetch
-#else
-#define PF_PENDING 0
-#endif
-#if defined(PROBE_NOBARRIER) && defined(PROBE_NOGLOAD)
-#define PROBE_BAR(x)
-#else
-#define PROBE_BAR(x) x
-#endif
 
 struct Params {
   const uint16_t* A; int64_t lda; int M;
@@ -96,11 +71,7 @@ struct Params {
 // each with its own L2; 32 consecutive workgroups of one XCD form an 8 x 4
 // super-tile so that they share operand panels in that L2, and super-tiles are
 // numbered N-fastest so that the XCDs walk the same A rows at the same time.
-#ifndef SUPM
-#define SUPM 8
-#define SUPN 4
-#endif
-constexpr int SUP_M = SUPM, SUP_N = SUPN, NXCD = 8;
+constexpr int SUP_M = 8, SUP_N = 4, NXCD = 8;
 __host__ __device__ inline int num_blocks(int Mt, int Nt) {
   int s = ((Mt + SUP_M - 1) / SUP_M) * ((Nt + SUP_N - 1) / SUP_N);
   return (s + NXCD - 1) / NXCD * NXCD * (SUP_M * SUP_N);
@@ -125,8 +96,11 @@ __device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 // The MFMA is issued through inline assembly with the accumulator tied in place in an
 // accumulation register: left to the register allocator, a few of the 64 accumulator tuples
 // (which fill the accumulation file completely) end up rotating through copies every iteration.
-// Consecutive MFMAs here never touch the same accumulator, so no wait states are needed
-// between them; the reads after the K loop are fenced by drain_mfma() below.
+// The K loop issues the two 32-wide K steps of an accumulator back to back: the second MFMA reads
+// as SrcC the register tuple the first one writes as vDst.  That dependent pair with identical
+// SrcC / vDst is the case the hardware interlocks by itself (no software wait states required);
+// no other instruction touches an accumulator inside the loop.  The first ordinary reads after
+// the K loop are fenced by drain_mfma() below.
 __device__ __forceinline__ void mfma16(f32x4& c, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
@@ -137,15 +111,8 @@ __device__ __forceinline__ void drain_mfma(f32x4 (&r)[8]) {
                : "+a"(r[0]), "+a"(r[1]), "+a"(r[2]), "+a"(r[3]), "+a"(r[4]), "+a"(r[5]), "+a"(r[6]), "+a"(r[7]));
 }
 
-#ifdef PROBE_CLOCK
-__device__ unsigned long long g_probe_clk[4];
-#endif
-
 template <int MODE>
 __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
-#ifdef PROBE_CLOCK
-  const unsigned long long c0 = clock64(), w0 = wall_clock64();
-#endif
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -167,9 +134,6 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
   int tm, tn, sm, sn;
   if (!tile_coords(blockIdx.x, Mt, Nt, tm, tn, sm, sn)) return;
-#ifdef PROBE_SAMETILE
-  tm = 0; tn = 0;
-#endif
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M || n0 >= N) return;
 
@@ -242,43 +206,6 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     }
   };
 
-  // ---- L2 prefetch (PF_DIST > 0; off in the library build).  The 32 workgroups of a super-tile
-  // run on one XCD and read the same 8 A and 4 B panels per K step; whoever asks first for a
-  // 128-byte line waits for the fabric (memory-side cache or HBM), longer than the double buffer
-  // covers.  With the prefetch each workgroup touches a share of the super-tile's lines PF_DIST
-  // panels ahead: one direct load of 4 bytes per lane into an LDS pad nobody reads, one 128-byte
-  // line (a row's whole K panel) per lane; waves 0 / 2 cover a quarter of the A rows each (two
-  // workgroups per line), waves 1 / 3 an eighth of the B rows in each half wave.
-  // On constant data (chip at full clock) this removes a quarter of the loop's stall cycles
-  // (1480 -> 1900 TFLOP/s on the dH shape).  On real data the chip is power-limited, fewer stall
-  // cycles only lower the clock, and the extra L2 -> L1 traffic of the prefetch (half as much
-  // again as the operands themselves) costs energy: the same kernels run 1.5 % (forward) to
-  // 6 % (dH) faster without it.
-  const uint16_t* pf_ptr;
-  {
-    int r;
-    if ((wave & 1) == 0) {
-      r = ((sn + wave) & 3) * 64 + lane;
-      if (A_KMAJOR) {                    // 64 k rows of four 128-byte lines
-        pf_ptr = p.A + (int64_t)(r >> 2) * p.lda + m0 + (r & 3) * 64;
-      } else {
-        r += m0; r = r < M ? r : M - 1;
-        pf_ptr = p.A + (int64_t)r * p.lda;
-      }
-    } else {
-      r = n0 + ((sm + (wave - 1) + 4 * (lane >> 5)) & 7) * 32 + (lane & 31); r = r < N ? r : N - 1;
-      int64_t rowb = r;
-      if (MODE == MODE_FWD) rowb = p.row_index[r];
-      pf_ptr = p.B + rowb * p.ldb;
-    }
-  }
-  const int64_t pf_kstep = (wave & 1) == 0 ? a_kstep : (int64_t)BK;
-  const uint32_t pf_lds = __builtin_amdgcn_readfirstlane(lds_base + PIPE_BYTES + wave * 256);
-  auto prefetch = [&](int kt) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(pf_ptr + kt * pf_kstep), "s"(pf_lds) : "memory");
-  };
-
   // ---- fragment read offsets.  A 16x16x32 operand fragment: lane -> row (lane & 15),
   // 16-byte K chunk (lane >> 4) of a 32-wide K step.  A 128-bit LDS read is served 16 lanes
   // per cycle over 64 banks; rows 2 apart share a bank window (128-byte rows), the swizzle
@@ -308,11 +235,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     a_tr_base = k * 512 + wm * 256 + (kswz(k) << 5) + ((frow & 2) << 3) + ((frow & 1) << 3);
   }
   auto read_a = [&](int st, int ks, int ib) -> bf16x8 {
-#ifdef PROBE_TRASB128
-    if (false) {
-#else
     if (A_KMAJOR) {
-#endif
       typedef short v4i16 __attribute__((ext_vector_type(4)));
       typedef short v8i16 __attribute__((ext_vector_type(8)));
       typedef __attribute__((address_space(3))) v4i16* lds_v4i16;
@@ -362,7 +285,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st + lds_a[j >> 1]);
     }
   };
-  auto panel = [&](int set, int st_cur, int st_nxt, int kt_load, int slot_load, int kt_pre) {
+  auto panel = [&](int set, int st_cur, int st_nxt, int kt_load, int slot_load) {
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
 #pragma unroll
@@ -372,18 +295,17 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       }
       __builtin_amdgcn_sched_barrier(0);
       if (g == 4) {
-        // this thread's part of panel kt+1 has landed (loads complete in order: only the prefetch
-        // issued after them may still be in flight), then everyone's; every wave has issued its
+        // this thread's part of panel kt+1 has landed, then everyone's; every wave has issued its
         // last read of panel kt's slot a group ago, so the slot can be refilled
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(PF_PENDING));
-        PROBE_BAR(__syncthreads());
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __syncthreads();
       }
       if (g < 4) {
-        PROBE_RD(fax[g & 3][0] = read_a(st_cur, 0, g + 4));
-        PROBE_RD(fax[g & 3][1] = read_a(st_cur, 1, g + 4));
+        fax[g & 3][0] = read_a(st_cur, 0, g + 4);
+        fax[g & 3][1] = read_a(st_cur, 1, g + 4);
       } else {
-        PROBE_RD(fax[g & 3][0] = read_a(st_nxt, 0, g - 4));
-        PROBE_RD(fax[g & 3][1] = read_a(st_nxt, 1, g - 4));
+        fax[g & 3][0] = read_a(st_nxt, 0, g - 4);
+        fax[g & 3][1] = read_a(st_nxt, 1, g - 4);
       }
       if (g >= 4) {
         // next B set in groups 4-6: column blocks 0-2, 3-5, 6-7, so that the last of them are
@@ -392,12 +314,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         if (g < 7) {
 #pragma unroll
           for (int j = (g - 4) * 3; j < (g == 6 ? 8 : (g - 3) * 3); ++j) {
-            PROBE_RD(fbx[set ^ 1][0][j] = read_b(st_nxt, 0, j));
-            PROBE_RD(fbx[set ^ 1][1][j] = read_b(st_nxt, 1, j));
+            fbx[set ^ 1][0][j] = read_b(st_nxt, 0, j);
+            fbx[set ^ 1][1][j] = read_b(st_nxt, 1, j);
           }
         }
-        PROBE_LD(issue_range(kt_load, slot_load, (g - 4) * 4, (g - 3) * 4));
-        if (PF_DIST > 0 && g == 7) { PROBE_LD(prefetch(kt_pre)); }
+        issue_range(kt_load, slot_load, (g - 4) * 4, (g - 3) * 4);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -413,23 +334,18 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
     issue_range(last_k(1), 1, 0, 16);
-    // keeps the invariant of the loop: one prefetch follows the last load of every panel
-    if (PF_PENDING) prefetch(last_k(PF_DIST));
 #pragma unroll
     for (int j = 0; j < 8; ++j) { fbx[0][0][j] = read_b(0, 0, j); fbx[0][1][j] = read_b(0, 1, j); }
 #pragma unroll
     for (int i = 0; i < 4; ++i) { fax[i][0] = read_a(0, 0, i); fax[i][1] = read_a(0, 1, i); }
     for (int kt = 0; kt < nk; kt += 2) {
-      panel(0, 0, STAGE_BYTES, last_k(kt + 2), 0, last_k(kt + PF_DIST));
-      panel(1, STAGE_BYTES, 0, last_k(kt + 3), 1, last_k(kt + 1 + PF_DIST));
+      panel(0, 0, STAGE_BYTES, last_k(kt + 2), 0);
+      panel(1, STAGE_BYTES, 0, last_k(kt + 3), 1);
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
     drain_mfma(acc[7]);
   }
 
-#ifdef PROBE_CLOCK
-  if (blockIdx.x == 8 && threadIdx.x == 0) { g_probe_clk[0] = clock64() - c0; g_probe_clk[1] = wall_clock64() - w0; }
-#endif
   // ---- epilogues.  Accumulator element (i, j, e) of this lane is
   //   row m = m0 + wm*128 + i*16 + 4*(lane>>4) + e      (FWD: the permuted row, see vrow below)
   //   col n = n0 + wn*128 + j*16 + (lane & 15)
