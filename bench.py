@@ -121,7 +121,7 @@ def main():
     import torch
 
     import paper_2605_07244_amd as mrl
-    from paper_2605_07244_amd import synth
+    from workloads import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)

@@ -1,76 +1,81 @@
 """CPU oracle for the THL word-level trace alignment (TEST INFRASTRUCTURE, not the product).
 
-The tokenizer-heterogeneity layer maps a source model's per-token log-probabilities
-onto the target model's token positions: source log-probs are summed per textual
-word and each word total is spread evenly over the target tokens of that word
-(Sec. 4.3; App. D, "THL WordAlignLogProbs", Alg. 2).  This module is the
-redistribution part of that routine on integer word maps; producing the maps
-(regular-expression spans and incremental tokenization, Alg. 1 and Alg. 3) needs
+The tokenizer-heterogeneity layer carries a source model's per-token log-probabilities over
+to the target model's token grid through the words both tokenizations share (Sec. 4.3):
+
+    Z_w        = sum over source response tokens s that belong to word w of  l_src[s]
+    C_w        = number of target response tokens that belong to word w
+    l_tilde[t] = Z_w(t) / max(1, C_w(t))        for a target response token t of word w(t)
+
+(Thm. 1 calls a response token valid when the response mask includes it and the word map
+assigns it a word; every other position carries no aligned value.)  This module evaluates that
+definition with word-membership indicator matrices, one sequence at a time in fp64: the sums
+over "tokens of word w" are literally rows of a 0/1 matrix times the log-prob vector.  Building
+the word maps themselves (word spans, incremental tokenisation; App. D, Alg. 1 and 3) needs
 tokenizers and text and is outside the hot path.
 
-The implementation takes the algorithm's steps in the paper's order and notation,
-with plain Python loops and dictionaries (small cases only).  Only tests, the
-smoke check and the bench's CPU-baseline leg may import it; it shares no code
-with the HIP path.
+Conventions for the cases the definition leaves open, as stated properties:
+  * a word map lists one entry per response token, in order; when the map and the response
+    mask disagree in length, only the first min(#response tokens, map length) tokens are valid
+    (App. D pairs map entries with response positions one to one);
+  * map entry -1 marks a token that belongs to no word (a leading delimiter);
+  * a target word no source token belongs to has Z_w = 0, so its tokens receive 0;
+  * a sequence whose source side has no valid token at all yields no aligned trace: every
+    position keeps `ignore_value`;
+  * every position that is not a valid target token keeps `ignore_value`.
 
-Parity status: pinned by tests/test_thl_oracle_pins.py (conservation of Thm. 1,
-the residual identity of Thm. 1, the closed formula of Sec. 4.3 evaluated by an
-independent vectorised routine, identity under equal segmentations, a
-hand-worked example, brute force).
+Only tests, the smoke check and the bench's CPU-baseline leg may import this module; it shares
+no code with the HIP path.
+
+Parity status: pinned by tests/test_thl_oracle_pins.py (a hand-worked instance, per-word
+conservation and the residual identity of Thm. 1, an independent evaluation by per-token
+loops, identity under equal segmentations, the ratio envelope of the corollary to Thm. 1).
 """
 from __future__ import annotations
 
 import numpy as np
 
-NONE = -1   # "None" entries of a word map (leading delimiter tokens, App. D)
+NONE = -1   # map entry of a token that belongs to no word
+
+
+def _valid_tokens(mask_row, map_row, map_len):
+    """Positions of the valid response tokens of one sequence and the word of each."""
+    pos = np.flatnonzero(np.asarray(mask_row) != 0)
+    n = min(pos.size, int(map_len))
+    words = np.asarray(map_row[:n], dtype=np.int64)
+    has_word = words != NONE
+    return pos[:n][has_word], words[has_word]
+
+
+def _membership(words, n_words):
+    """0/1 matrix [n_words, n_tokens]: entry (w, k) is 1 when token k belongs to word w."""
+    return (words[None, :] == np.arange(n_words, dtype=np.int64)[:, None]).astype(np.float64)
 
 
 def word_align_logprobs(source_log_probs, source_response_mask, src_word_map, src_map_len,
                         target_response_mask, tgt_word_map, tgt_map_len, ignore_value):
-    """Alg. 2 (App. D) on integer word maps.
+    """Word-level trace alignment of Sec. 4.3 on integer word maps.
 
     source_log_probs      [B, S_src] float
     source_response_mask  [B, S_src] 0/1
-    src_word_map          [B, S_src] int; entry p (p < src_map_len[i]) is the word index of
-                          the p-th response token of sequence i, or NONE
-    src_map_len           [B] int, the length |src_ids| of the map of sequence i
+    src_word_map          [B, S_src] int; entry p (p < src_map_len[i]) is the word of the p-th
+                          response token of sequence i, or NONE
+    src_map_len           [B] int
     target_*              likewise on the target grid
-    Returns out [B, S_tgt] float64: ignore_value everywhere except at the target response
-    positions that carry a word, which get (sum of the word's source log-probs) / (number
-    of target tokens of the word); a word no source token maps to has sum 0.
-    A sequence whose source side has no token with a word stays all ignore_value.
+    Returns l_tilde [B, S_tgt] float64, `ignore_value` wherever no aligned value is defined.
     """
-    src_lp = np.asarray(source_log_probs, dtype=np.float64)
-    src_m = np.asarray(source_response_mask)
-    tgt_m = np.asarray(target_response_mask)
-    B = src_lp.shape[0]
-    out = np.full(tgt_m.shape, float(ignore_value), dtype=np.float64)
-    for i in range(B):
-        src_idx = [j for j in range(src_m.shape[1]) if src_m[i, j] == 1]
-        tgt_idx = [j for j in range(tgt_m.shape[1]) if tgt_m[i, j] == 1]
-        L_src = min(len(src_idx), int(src_map_len[i]))
-        L_tgt = min(len(tgt_idx), int(tgt_map_len[i]))
-        per_word_sum = {}
-        for p in range(L_src):
-            wid = int(src_word_map[i][p])
-            if wid == NONE:
-                continue
-            per_word_sum[wid] = per_word_sum.get(wid, 0.0) + src_lp[i, src_idx[p]]
-        if not per_word_sum:
+    l_src = np.asarray(source_log_probs, dtype=np.float64)
+    tgt_mask = np.asarray(target_response_mask)
+    aligned = np.full(tgt_mask.shape, float(ignore_value), dtype=np.float64)
+    for i in range(l_src.shape[0]):
+        s_pos, s_word = _valid_tokens(source_response_mask[i], src_word_map[i], src_map_len[i])
+        t_pos, t_word = _valid_tokens(tgt_mask[i], tgt_word_map[i], tgt_map_len[i])
+        if s_pos.size == 0 or t_pos.size == 0:
             continue
-        per_word_count = {}
-        for p in range(L_tgt):
-            wid = int(tgt_word_map[i][p])
-            if wid == NONE:
-                continue
-            per_word_count[wid] = per_word_count.get(wid, 0) + 1
-        for p in range(L_tgt):
-            wid = int(tgt_word_map[i][p])
-            if wid == NONE:
-                continue
-            cnt = per_word_count.get(wid, 0)
-            if cnt <= 0:
-                continue
-            out[i, tgt_idx[p]] = per_word_sum.get(wid, 0.0) / cnt
-    return out
-
+        n_words = int(max(s_word.max(), t_word.max())) + 1
+        in_src = _membership(s_word, n_words)            # [n_words, valid source tokens]
+        in_tgt = _membership(t_word, n_words)            # [n_words, valid target tokens]
+        Z = in_src @ l_src[i, s_pos]                     # word mass
+        C = in_tgt.sum(axis=1)                           # target tokens per word
+        aligned[i, t_pos] = in_tgt.T @ (Z / np.maximum(1.0, C))
+    return aligned

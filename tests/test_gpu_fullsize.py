@@ -24,7 +24,7 @@ KINK_MARGIN = 5e-3
 
 def _run_full(idx, **over):
     import paper_2605_07244_amd as mrl
-    from paper_2605_07244_amd import synth
+    from workloads import synth
     sp = synth.spec(idx, **over)
     b = synth.make(sp, "cuda")
     B, T, G, N, V, d = (b[k] for k in ("B", "T", "G", "N", "V", "d"))
@@ -151,7 +151,7 @@ def test_config5_scoring_pass_full_size_sampled():
     """Forward-only scoring pass (log-prob, lse, entropy) on configuration 5 as bench.py runs it:
     sampled scored rows against the oracle, and size-independent properties for all rows."""
     import paper_2605_07244_amd as mrl
-    from paper_2605_07244_amd import synth
+    from workloads import synth
     sp = synth.spec(5)
     b = synth.make(sp, "cuda")
     mask = b["mask"].reshape(-1)

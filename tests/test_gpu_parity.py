@@ -19,7 +19,7 @@ def mrl():
 
 @pytest.fixture(scope="module")
 def synth():
-    from paper_2605_07244_amd import synth as s
+    from workloads import synth as s
     return s
 
 

@@ -531,6 +531,48 @@ def test_clip_statistics_definitions():
     assert res["n_scored_tokens"] == int(m.sum())
 
 
+def test_ratio_and_k3_means_run_over_grpo_tokens_only():
+    """mean_ratio, max_ratio, mean_k3 and the clip counts are statistics of the scored tokens of
+    GRPO rows (App. E.3, token-ratio table: mean / p99 / clip rate of the importance ratio over the
+    response tokens that enter Eq. 1).  Written out as a literal loop with an auxiliary SGT row and
+    an empty row in the batch: dividing by all scored tokens, by all slots, or letting the SGT
+    row's tokens in would each give a different number."""
+    t = _tiny(24, B=6, T=5, G=3)
+    kind = np.array([0, 1, 0, 0, 1, 0])
+    t["m"][3, :] = False                                   # an empty GRPO row
+    t["behav"] = t["behav"] + np.where(np.repeat(kind, t["T"]) == 1, 1.7, 0.0)   # SGT rows would move every statistic
+    res = _run(t, seq_kind=kind)
+    logp = res["logp"].reshape(t["B"], t["T"])
+    beh, ref = t["behav"].reshape(t["B"], t["T"]), t["ref"].reshape(t["B"], t["T"])
+    n = 0
+    sum_w = sum_k3 = 0.0
+    max_w = 0.0
+    n_clip = 0
+    for b in range(t["B"]):
+        if kind[b] != 0:
+            continue
+        for s in range(t["T"]):
+            if not t["m"][b, s]:
+                continue
+            w = float(np.exp(logp[b, s] - beh[b, s]))
+            rho = float(ref[b, s] - logp[b, s])
+            n += 1
+            sum_w += w
+            sum_k3 += np.exp(rho) - rho - 1.0
+            max_w = max(max_w, w)
+            n_clip += int(w < 0.8 or w > 1.2)
+    n_all = int(t["m"].sum())
+    assert 0 < n < n_all                                   # the SGT rows hold scored tokens too
+    assert abs(res["mean_ratio"] - sum_w / n) < 1e-14
+    assert abs(res["mean_k3"] - sum_k3 / n) < 1e-14
+    assert abs(res["max_ratio"] - max_w) < 1e-15
+    assert res["n_clipped_tokens"] == n_clip
+    assert res["n_scored_tokens"] == n_all
+    # the wrong denominators are far outside the tolerance above
+    assert abs(res["mean_ratio"] - sum_w / n_all) > 1e-3
+    assert abs(res["mean_k3"] - sum_k3 / n_all) > 1e-6
+
+
 # ---------------------------------------------------------------- P5 finite differences
 @pytest.mark.parametrize("seed,kind", [(30, None), (31, np.array([0, 0, 0, 1]))])
 def test_gradients_by_central_differences(seed, kind):

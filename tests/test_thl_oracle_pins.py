@@ -1,4 +1,4 @@
-"""Pins of the THL alignment oracle (App. D, Alg. 2) against what the paper and the
+"""Pins of the THL alignment oracle (Sec. 4.3 formula; App. D) against what the paper and the
 mathematics fix.  None of these tests touches the HIP path."""
 import os
 
@@ -108,8 +108,8 @@ def test_sequence_residual_identity(seed):
 
 @pytest.mark.parametrize("seed", range(4))
 def test_closed_formula_vectorised(seed):
-    """Sec. 4.3: aligned value = m_t * Z_{w(t)} / max(1, C_{w(t)}), evaluated with bincount
-    instead of the algorithm's dictionaries."""
+    """Sec. 4.3: aligned value = m_t * Z_{w(t)} / max(1, C_{w(t)}), evaluated with histogram
+    sums (bincount) instead of the oracle's indicator-matrix products."""
     src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len = _random_case(seed + 200)
     out = thl.word_align_logprobs(src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len, IGN)
     for i in range(src_lp.shape[0]):
@@ -123,6 +123,36 @@ def test_closed_formula_vectorised(seed):
             has = tw >= 0
             expect[tidx[has]] = Z[tw[has]] / np.maximum(1, C[tw[has]])
         assert np.allclose(out[i], expect, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_per_token_brute_force(seed):
+    """For every target position separately: scan all source positions for tokens of the same word
+    (Z), scan all target positions for tokens of the same word (C).  Quadratic, no shared
+    bookkeeping between positions, walks the masks position by position."""
+    src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len = _random_case(seed + 300, B=4, S_src=24, S_tgt=30)
+    out = thl.word_align_logprobs(src_lp, src_m, src_map, src_len, tgt_m, tgt_map, tgt_len, IGN)
+
+    def word_at(mask_row, map_row, map_len, pos):
+        """Word of the token at `pos`, or None when it is not a valid response token."""
+        if mask_row[pos] != 1:
+            return None
+        rank = int(np.sum(mask_row[:pos] == 1))          # it is the rank-th response token
+        if rank >= map_len or map_row[rank] == thl.NONE:
+            return None
+        return int(map_row[rank])
+
+    for i in range(src_lp.shape[0]):
+        src_words = [word_at(src_m[i], src_map[i], src_len[i], s) for s in range(src_m.shape[1])]
+        any_source = any(w is not None for w in src_words)
+        for t in range(tgt_m.shape[1]):
+            w = word_at(tgt_m[i], tgt_map[i], tgt_len[i], t)
+            if w is None or not any_source:
+                assert out[i, t] == IGN
+                continue
+            Z = sum(src_lp[i, s] for s in range(src_m.shape[1]) if src_words[s] == w)
+            C = sum(1 for u in range(tgt_m.shape[1]) if word_at(tgt_m[i], tgt_map[i], tgt_len[i], u) == w)
+            assert abs(out[i, t] - Z / max(1, C)) < 1e-12
 
 
 def test_equal_segmentations_give_the_source_trace_back():
