@@ -28,39 +28,50 @@ def log(msg):
 
 
 def cpu_baseline(batch, sp, rows_T=256):
-    """Times the CPU oracle (as it stands) on a bounded sample of the same workload:
-    the first prompt's rollouts truncated to their first `rows_T` tokens, at full V and d."""
+    """Times the CPU oracle (as it stands) on a bounded sample of the same workload: the first
+    prompt's rollouts truncated to their first `rows_T` tokens, at full V and d, once with all the
+    threads NumPy's BLAS takes on this host and once confined to a single thread (on the first
+    eighth of those tokens: the oracle's cost is linear in the rows)."""
     import numpy as np
-    from threadpoolctl import threadpool_info
+    import torch
+    from threadpoolctl import threadpool_info, threadpool_limits
 
     from oracle import mrl_oracle as orc
     from tests import util
 
     T = batch["T"]
     k = sp.k_own + sp.k_peer
-    t_sub = min(rows_T, T)
-    rows = (np.arange(k)[:, None] * T + np.arange(t_sub)[None, :]).reshape(-1)
-    import torch
-    ridx = torch.tensor(rows, device=batch["H"].device)
-    H = util.to_f64(batch["H"][ridx])
     W = util.to_f64(batch["W"])
-    y = batch["targets"][ridx].cpu().numpy()
-    mask = batch["mask"].reshape(-1)[ridx].cpu().numpy().reshape(k, t_sub)
-    behav = util.to_f64(batch["behav"][ridx])
-    ref = util.to_f64(batch["ref"][ridx])
     rewards = util.to_f64(batch["rewards_all"][:k])
     gid = np.zeros(k, dtype=np.int64)
     cfg = util.cfg_dict(sp)
-    t0 = time.perf_counter()
-    adv, *_ = orc.group_advantages(rewards, gid, 1)
-    out = orc.grpo_loss_fwd_bwd(H, W, y, mask, behav, ref, adv, gid, None, k, t_sub, 1, cfg)
-    dt = time.perf_counter() - t0
-    n_tok = int(mask.sum())
+
+    def timed(t_sub):
+        rows = (np.arange(k)[:, None] * T + np.arange(t_sub)[None, :]).reshape(-1)
+        ridx = torch.tensor(rows, device=batch["H"].device)
+        H = util.to_f64(batch["H"][ridx])
+        y = batch["targets"][ridx].cpu().numpy()
+        mask = batch["mask"].reshape(-1)[ridx].cpu().numpy().reshape(k, t_sub)
+        behav, ref = util.to_f64(batch["behav"][ridx]), util.to_f64(batch["ref"][ridx])
+        t0 = time.perf_counter()
+        adv, *_ = orc.group_advantages(rewards, gid, 1)
+        out = orc.grpo_loss_fwd_bwd(H, W, y, mask, behav, ref, adv, gid, None, k, t_sub, 1, cfg)
+        dt = time.perf_counter() - t0
+        assert np.isfinite(out["loss_total"])
+        return int(mask.sum()), dt
+
+    t_all = min(rows_T, T)
+    n_tok, dt = timed(t_all)
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    assert np.isfinite(out["loss_total"])
+    t_one = max(1, t_all // 8)
+    with threadpool_limits(limits=1):
+        n_tok1, dt1 = timed(t_one)
     return dict(value=n_tok / dt, unit="tokens/s", cores=int(threads), kind="oracle",
-                sample=f"{k} sequences x first {t_sub} tokens ({n_tok} scored rows) at full V={sp.V}, d={sp.d}; "
-                       f"fp64 NumPy, {dt:.1f} s")
+                sample=f"{k} sequences x first {t_all} tokens ({n_tok} scored rows) at full V={sp.V}, d={sp.d}; "
+                       f"fp64 NumPy, {dt:.1f} s",
+                single_thread=dict(value=n_tok1 / dt1, unit="tokens/s", cores=1,
+                                   sample=f"{k} sequences x first {t_one} tokens ({n_tok1} scored rows), {dt1:.1f} s"),
+                host_cpus=os.cpu_count())
 
 
 def thl_alignment_leg(mrl, synth, torch, with_cpu, B=2048, S_src=1180, S_tgt=1536, reps=20):

@@ -11,7 +11,8 @@
  * Conventions for every entry point
  *   - Returns an mrl_status (0 = MRL_OK, negative = error).  Never throws,
  *     never aborts.  Arguments are validated on the host before any device
- *     work is enqueued; on error nothing has been launched.
+ *     work is enqueued; on error nothing has been launched (the two data-dependent
+ *     codes of the debug_sync mode of call (3) are the exception, see there).
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The
  *     library allocates no device memory: scratch space comes from the
  *     caller's workspace, whose size is obtained from the matching
@@ -19,7 +20,7 @@
  *   - Work is enqueued on the caller's stream (a hipStream_t passed as
  *     void*, NULL = the default stream) and is asynchronous: outputs are
  *     valid once the caller has synchronised that stream.  No host
- *     synchronisation happens inside a call.
+ *     synchronisation happens inside a call (debug_sync of call (3) excepted).
  *   - Inputs are never modified.  Outputs are fully overwritten, except
  *     out_dW when accumulate_dw = 1.
  *   - All tensors are dense and row-major.  lm_head_w is [V, d], one row per
@@ -48,8 +49,8 @@ typedef enum {
   MRL_ERR_NULL = -1,             /* a required pointer is NULL                          */
   MRL_ERR_SHAPE = -2,            /* a size is <= 0, too large, or violates a divisibility rule */
   MRL_ERR_DTYPE = -3,            /* unknown mrl_dtype                                   */
-  MRL_ERR_TARGET_RANGE = -4,     /* reserved: target ids are checked on the device (see stats) */
-  MRL_ERR_GROUP_RANGE = -5,      /* reserved: group ids are checked on the device       */
+  MRL_ERR_TARGET_RANGE = -4,     /* debug_sync only: a scored slot has a target id outside [0, V) */
+  MRL_ERR_GROUP_RANGE = -5,      /* debug_sync only: a sequence has a group id outside [0, G)     */
   MRL_ERR_WORKSPACE = -6,        /* workspace NULL, misaligned or too small             */
   MRL_ERR_CONFIG = -7,           /* a configuration value is out of its domain          */
   MRL_ERR_DEVICE = -8,           /* no usable device / a HIP call failed                */
@@ -168,6 +169,8 @@ int mrl_group_advantages(const float* rewards /*[B] dev*/, const int32_t* group_
  * L_b > 0.  loss_agg = 1: c = mask / (all scored GRPO tokens).
  * Backward: g = dL/dl; dz[n, v] = g[n] (1[v = y_n] - softmax[n, v]);
  * out_dH = dz W (rows of unscored slots are zero), out_dW (+)= dz^T H in fp32.
+ * Every reduction runs in a fixed order (no floating-point atomics): results are
+ * bit-reproducible from run to run, so there is no separate deterministic mode.
  * out_dH and/or out_dW may be NULL to skip that gradient.
  * ref_logp may be NULL when kl_beta = 0.  group_id[b] must lie in [0, G); a
  * row with an id outside gets weight 0.
@@ -197,7 +200,13 @@ typedef struct {
                             ratio statistics then count each token with its response's ratio.
                             They run the forward contraction twice (the response sums must be
                             complete before any token's gradient weight is known).           */
-  int32_t reserved;      /* must be 0 */
+  int32_t debug_sync;    /* 0 = fully asynchronous (default): target and group ids are range-checked on
+                            the device only, offenders are skipped and counted (n_bad_targets; a bad
+                            group id gives its row weight 0).
+                            1 = debugging aid: after the preparation kernels the call waits for the
+                            stream, reads the two counters back and returns MRL_ERR_TARGET_RANGE or
+                            MRL_ERR_GROUP_RANGE if either is non-zero; no GEMM has been enqueued then
+                            and the outputs hold nothing defined.  Not for timed or captured code.  */
 } mrl_loss_config;
 
 typedef struct {

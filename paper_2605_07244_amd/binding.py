@@ -36,7 +36,7 @@ class _LossConfig(ctypes.Structure):
     _fields_ = [("clip_eps_low", c_float), ("clip_eps_high", c_float), ("kl_beta", c_float),
                 ("sgt_lambda", c_float), ("loss_agg", c_int32), ("accumulate_dw", c_int32),
                 ("dh_dtype", c_int32), ("chunk_rows", c_int32), ("scored_rows_hint", c_int64),
-                ("ratio_level", c_int32), ("reserved", c_int32)]
+                ("ratio_level", c_int32), ("debug_sync", c_int32)]
 
 
 @dataclass
@@ -51,11 +51,12 @@ class LossConfig:
     chunk_rows: int = 0
     scored_rows_hint: int = 0
     ratio_level: int = 0
+    debug_sync: int = 0
 
     def to_c(self) -> _LossConfig:
         return _LossConfig(self.clip_eps_low, self.clip_eps_high, self.kl_beta, self.sgt_lambda,
                            self.loss_agg, self.accumulate_dw, self.dh_dtype, self.chunk_rows,
-                           self.scored_rows_hint, self.ratio_level, 0)
+                           self.scored_rows_hint, self.ratio_level, self.debug_sync)
 
 
 STATS_FIELDS = ("loss_total", "loss_pg", "loss_kl", "loss_sgt", "mean_ratio", "max_ratio", "mean_k3",

@@ -18,7 +18,7 @@ constexpr int64_t kMaxSlots = (int64_t)1 << 30;
 // ------------------------------------------------------------------ profiling
 struct ProfRec { int cls; hipEvent_t start, stop; };
 std::mutex g_prof_mu;
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};
 std::vector<ProfRec> g_prof_log;
 std::vector<hipEvent_t> g_event_pool;
 
@@ -32,14 +32,14 @@ hipEvent_t take_event() {
 }  // namespace
 
 void prof_begin(int cls, hipStream_t stream) {
-  if (!g_prof_on) return;
+  if (!g_prof_on.load(std::memory_order_relaxed)) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   ProfRec r{cls, take_event(), take_event()};
   (void)hipEventRecord(r.start, stream);
   g_prof_log.push_back(r);
 }
 void prof_end(int cls, hipStream_t stream) {
-  if (!g_prof_on) return;
+  if (!g_prof_on.load(std::memory_order_relaxed)) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   for (size_t i = g_prof_log.size(); i-- > 0;)
     if (g_prof_log[i].cls == cls) { (void)hipEventRecord(g_prof_log[i].stop, stream); break; }
@@ -153,7 +153,8 @@ int check_cfg(const mrl_loss_config* c) {
   if (c->dh_dtype != MRL_F32 && c->dh_dtype != MRL_BF16) return MRL_ERR_CONFIG;
   if (c->chunk_rows < 0 || c->chunk_rows % kTile != 0 || c->chunk_rows > (1 << 20)) return MRL_ERR_CONFIG;
   if (c->scored_rows_hint < 0) return MRL_ERR_CONFIG;
-  if (c->ratio_level < 0 || c->ratio_level > 2 || c->reserved != 0) return MRL_ERR_CONFIG;
+  if (c->ratio_level < 0 || c->ratio_level > 2) return MRL_ERR_CONFIG;
+  if (c->debug_sync != 0 && c->debug_sync != 1) return MRL_ERR_CONFIG;
   if (c->ratio_level != 0 && c->loss_agg != 0) return MRL_ERR_CONFIG;
   return MRL_OK;
 }
@@ -238,7 +239,7 @@ int mrl_version(void) { return 100; }
 
 int mrl_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  g_prof_on = on != 0;
+  g_prof_on.store(on != 0);
   return MRL_OK;
 }
 
@@ -402,10 +403,23 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     PrepOut po = {row_index, n_scored, n_scored + 1, at<int32_t>(ws, L.block_counts)};
     launch_prep(token_mask, target_ids, N, V, po, s);
     launch_seq_weights(token_mask, target_ids, group_id, seq_kind, B, T, G, V, cfg->loss_agg,
-                       at<int32_t>(ws, L.seq_len), at<float>(ws, L.seq_coef), at<int32_t>(ws, L.group_count), s);
+                       at<int32_t>(ws, L.seq_len), at<float>(ws, L.seq_coef), at<int32_t>(ws, L.group_count),
+                       n_scored + 2, s);
     launch_zero_unscored(token_mask, target_ids, N, V, d, out_logp, nullptr, out_dH,
                          cfg->dh_dtype == MRL_BF16 ? 2 : 4, s);
     launch_target_logit(hidden, lm_head_w, target_ids, row_index, n_scored, N, d, bf16, at<float>(ws, L.zt), s);
+  }
+  if (cfg->debug_sync) {
+    // debugging aid: wait for the preparation kernels and turn the device-side range counters
+    // into error codes before any further work is enqueued
+    int64_t counters[3] = {0, 0, 0};
+    if (hipStreamSynchronize(s) != hipSuccess ||
+        hipMemcpy(counters, n_scored, sizeof(counters), hipMemcpyDeviceToHost) != hipSuccess) {
+      (void)hipGetLastError();
+      return MRL_ERR_DEVICE;
+    }
+    if (counters[1] != 0) return MRL_ERR_TARGET_RANGE;
+    if (counters[2] != 0) return MRL_ERR_GROUP_RANGE;
   }
   if (out_dH) {
     Scope sc(MRL_PROF_CONVERT, s);

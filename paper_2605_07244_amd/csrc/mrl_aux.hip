@@ -150,7 +150,8 @@ __global__ __launch_bounds__(256) void k_seq_len(const uint8_t* mask, const int3
 
 __global__ __launch_bounds__(1024) void k_seq_coef(const int32_t* seq_len, const int32_t* group_id,
                                                   const uint8_t* seq_kind, int64_t B, int G,
-                                                  int loss_agg, int32_t* group_count, float* seq_coef) {
+                                                  int loss_agg, int32_t* group_count, float* seq_coef,
+                                                  int64_t* n_bad_groups) {
   __shared__ long long sh_a[1024];
   __shared__ long long sh_b[1024];
   __shared__ long long tot_aux, tot_tok, tot_groups;
@@ -187,6 +188,16 @@ __global__ __launch_bounds__(1024) void k_seq_coef(const int32_t* seq_len, const
   }
   if (threadIdx.x == 0) tot_groups = sh_a[0];
   __syncthreads();
+  // sequences whose group id is out of range (they get weight 0 below)
+  long long nbad = 0;
+  for (int64_t b = threadIdx.x; b < B; b += 1024) nbad += (group_id[b] < 0 || group_id[b] >= G);
+  sh_b[threadIdx.x] = nbad;
+  __syncthreads();
+  for (int off = 512; off > 0; off >>= 1) {
+    if (threadIdx.x < off) sh_b[threadIdx.x] += sh_b[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *n_bad_groups = sh_b[0];
   const double P = (double)tot_groups, S = (double)tot_aux, NT = (double)tot_tok;
   for (int64_t b = threadIdx.x; b < B; b += 1024) {
     const int kind = seq_kind ? seq_kind[b] : 0;
@@ -668,10 +679,11 @@ void launch_prep(const uint8_t* mask, const int32_t* targets, int64_t N, int V, 
 
 void launch_seq_weights(const uint8_t* mask, const int32_t* targets, const int32_t* group_id,
                         const uint8_t* seq_kind, int64_t B, int T, int G, int V, int loss_agg,
-                        int32_t* seq_len, float* seq_coef, int32_t* group_count, hipStream_t stream) {
+                        int32_t* seq_len, float* seq_coef, int32_t* group_count, int64_t* n_bad_groups,
+                        hipStream_t stream) {
   hipLaunchKernelGGL(k_seq_len, dim3((unsigned)B), dim3(256), 0, stream, mask, targets, T, V, seq_len);
   hipLaunchKernelGGL(k_seq_coef, dim3(1), dim3(1024), 0, stream, seq_len, group_id, seq_kind, B, G, loss_agg,
-                     group_count, seq_coef);
+                     group_count, seq_coef, n_bad_groups);
 }
 
 void launch_seq_log_ratio(const uint8_t* mask, const int32_t* targets, const float* logp,

@@ -79,7 +79,8 @@ struct PrepOut {
   int32_t* row_index;   // [N] compacted scored slots, in slot order; tail filled with 0
   int64_t* n_scored;    // [1]
   int64_t* n_bad;       // [1] masked-in slots with a target outside [0, V)
-  int32_t* block_counts; // scratch [ceil(N / 1024) + 1]
+  int32_t* block_counts; // scratch: per 1024-slot block a scored count and a bad-target count (int32),
+                         // followed, 8-byte aligned, by the blocks' exclusive offsets (int64)
 };
 void launch_prep(const uint8_t* mask, const int32_t* targets, int64_t N, int V, const PrepOut& o,
                  hipStream_t stream);
@@ -90,6 +91,7 @@ void launch_prep(const uint8_t* mask, const int32_t* targets, int64_t N, int V, 
 void launch_seq_weights(const uint8_t* mask, const int32_t* targets, const int32_t* group_id,
                         const uint8_t* seq_kind, int64_t B, int T, int G, int V, int loss_agg,
                         int32_t* seq_len, float* seq_coef, int32_t* group_count /*[G] scratch*/,
+                        int64_t* n_bad_groups /*[1]: sequences whose group id is outside [0, G)*/,
                         hipStream_t stream);
 
 // Response-level log-ratio (App. I.1): seq_expo[b] = sum over the scored tokens of sequence b of

@@ -98,6 +98,32 @@ def test_bad_targets_are_treated_as_masked(mrl, synth):
     assert util.rel_fro(util.to_f64(out["dW"]), want["dW"]) <= util.REL_TOL
 
 
+def test_debug_sync_turns_range_counters_into_error_codes(mrl, synth):
+    """The synchronous debugging mode of the loss call: a scored slot with a target id outside
+    [0, V) returns MRL_ERR_TARGET_RANGE (-4), a sequence with a group id outside [0, G)
+    MRL_ERR_GROUP_RANGE (-5), clean inputs run as usual and give the same bits as the asynchronous
+    mode."""
+    sp, b = _small(synth)
+    clean = _gpu_loss(mrl, sp, b, cfg=dict(debug_sync=1))
+    ref = _gpu_loss(mrl, sp, b)
+    assert torch.equal(clean["logp"], ref["logp"]) and torch.equal(clean["dW"], ref["dW"])
+    targets = b["targets"].clone()
+    first = torch.nonzero(b["mask"].reshape(-1))[0, 0]
+    targets[first] = b["V"] + 5
+    with pytest.raises(mrl.MrlError) as e:
+        _gpu_loss(mrl, sp, b, targets=targets, cfg=dict(debug_sync=1))
+    assert e.value.status == -4
+    bb = dict(b)
+    bb["seq_group"] = b["seq_group"].clone()
+    bb["seq_group"][3] = b["G"]
+    with pytest.raises(mrl.MrlError) as e:
+        _gpu_loss(mrl, sp, bb, cfg=dict(debug_sync=1))
+    assert e.value.status == -5
+    # the asynchronous mode skips the offenders instead
+    out = _gpu_loss(mrl, sp, b, targets=targets)
+    assert out["st"]["n_bad_targets"] == 1
+
+
 def test_accumulate_dw_and_optional_gradients(mrl, synth):
     sp, b = _small(synth)
     base = _gpu_loss(mrl, sp, b)

@@ -3,7 +3,11 @@
 The CPU oracle cannot run N x V = 10^11 logits, so it computes, from the inputs alone,
 (i) the log-prob, (ii) dL/dl and (iii) the dH row of SAMPLED scored tokens (one row of
 logits each, fp64), and the whole-batch quantities that need no vocabulary work
-(weights, counts).  Everything else is checked through properties that hold at any size:
+(weights, counts).  The O(N) part of the step (Eq. 1 / Eq. 2 terms, statistics) is recomputed by
+the oracle for ALL rows from the log-probs the GPU returned (validated on the sampled rows), and
+SAMPLED VOCABULARY ROWS of dW are recomputed by the oracle's formula over all scored rows, with
+each row's log-sum-exp taken as (fp64 target logit) - (that validated log-prob).
+Everything else is checked through properties that hold at any size:
   * <dH, H> = <dW, W>  (both equal sum_n,v dz[n,v] z[n,v]),
   * sum_v dW[v, :] = 0 (each dz row sums to zero),
   * unscored slots have zero log-prob and zero dH rows,
@@ -86,6 +90,61 @@ def _check_sampled(sp, b, seq_adv, out, st, n_scored):
     return mflat
 
 
+def _check_epilogue_all_rows(sp, b, seq_adv, out, st):
+    """Eq. (1) / Eq. (2) terms and statistics for every row: the oracle's O(N) part evaluated in
+    fp64 on the log-probs the GPU produced."""
+    B, T, G = b["B"], b["T"], b["G"]
+    cfg = util.cfg_dict(sp)
+    want = orc.loss_from_logp(out["logp"].cpu().numpy().astype(np.float64), b["mask"].cpu().numpy().reshape(B, T),
+                              util.to_f64(b["behav"]), util.to_f64(b["ref"]), seq_adv.cpu().numpy().astype(np.float64),
+                              b["seq_group"].cpu().numpy(), b["seq_kind"].cpu().numpy(), B, T, G, cfg)
+    util.check_loss_terms(st, want, sp.kl_beta, sp.sgt_lambda)
+    n = max(want["n_scored_tokens"], 1)
+    # fp32 and fp64 may disagree on tokens whose ratio sits within rounding of a clip edge
+    assert abs(st["n_clipped_tokens"] - want["n_clipped_tokens"]) <= max(2, int(2e-5 * n))
+    assert abs(st["n_zero_grad_tokens"] - want["n_zero_grad_tokens"]) <= max(2, int(2e-5 * n))
+    assert abs(st["mean_ratio"] - want["mean_ratio"]) <= 1e-5 * want["mean_ratio"]
+    assert abs(st["max_ratio"] - want["max_ratio"]) <= 1e-5 * want["max_ratio"]
+    assert abs(st["mean_k3"] - want["mean_k3"]) <= 1e-4 * want["mean_k3"]
+    return want
+
+
+def _check_dw_sampled_vocab_rows(sp, b, out, g_all, n_rows=16, chunk=32768):
+    """dW[v, :] = sum_n g_n (1[y_n = v] - exp(z[n, v] - lse_n)) H[n, :] for sampled vocabulary ids
+    v, over all scored rows n, in fp64 on the host, chunk by chunk.  lse_n = <H_n, W_{y_n}> (fp64)
+    minus the GPU's log-prob of the row; g_n is the oracle's dL/dl evaluated on those log-probs.
+    The sample always holds the last id of the vocabulary (ragged last tile when V % 256 != 0), id 0,
+    ids that are targets of some scored row, and ids that are nobody's target."""
+    V, d = b["V"], b["d"]
+    m = b["mask"].reshape(-1).bool()
+    rows = torch.nonzero(m)[:, 0]
+    y_all = b["targets"][rows].long()
+    rng = np.random.default_rng(4321 + sp.index)
+    hit = torch.unique(y_all).cpu().numpy()
+    vs = np.unique(np.concatenate([[0, V - 1, V - 2, V // 256 * 256 - 1, min(V - 1, V // 256 * 256)],
+                                   rng.choice(hit, size=n_rows // 2, replace=False),
+                                   rng.integers(0, V, size=n_rows // 2)]))
+    Wv = util.to_f64(b["W"][torch.tensor(vs, device="cuda")])          # [n_v, d]
+    logp_g = out["logp"]
+    ref = np.zeros((vs.size, d))
+    for r0 in range(0, rows.numel(), chunk):
+        rr = rows[r0:r0 + chunk]
+        Hc = util.to_f64(b["H"][rr])
+        yc = b["targets"][rr].long()
+        Wy = util.to_f64(b["W"][yc])
+        zt = np.einsum("nk,nk->n", Hc, Wy)
+        lse = zt - logp_g[rr].cpu().numpy().astype(np.float64)
+        z = Hc @ Wv.T                                                   # [rows, n_v]
+        dz = -g_all[rr.cpu().numpy()][:, None] * np.exp(z - lse[:, None])
+        yc_np = yc.cpu().numpy()
+        for j, v in enumerate(vs):
+            sel = yc_np == v
+            dz[sel, j] += g_all[rr.cpu().numpy()][sel]
+        ref += dz.T @ Hc
+    got = util.to_f64(out["dW"][torch.tensor(vs, device="cuda")])
+    util.check_gradient(f"dW[{vs.size} sampled vocabulary rows]", got, ref)
+
+
 def _check_properties(sp, b, out, st, n_scored, mflat):
     N, V, d = b["N"], b["V"], b["d"]
     assert st["n_scored_tokens"] == n_scored and st["n_unprocessed_rows"] == 0 and st["n_bad_targets"] == 0
@@ -122,28 +181,34 @@ def _check_properties(sp, b, out, st, n_scored, mflat):
 def test_config2_full_size_sampled():
     mrl, sp, b, seq_adv, out, st, n_scored = _run_full(2)
     mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    want = _check_epilogue_all_rows(sp, b, seq_adv, out, st)
+    _check_dw_sampled_vocab_rows(sp, b, out, want["g"])
     _check_properties(sp, b, out, st, n_scored, mflat)
 
 
-def test_config3_prp_pool_full_width_sampled():
-    # PRP pooled batch (own + peer rollouts in one group, heavy-tailed peer ratios) at full V and d, 8 of 32 prompts
-    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(3, n_prompts=8)
+def test_config3_prp_pool_full_size_sampled():
+    # PRP pooled batch (own + peer rollouts in one group, heavy-tailed peer ratios), all 32 prompts
+    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(3)
     assert st["n_clipped_tokens"] > 0.2 * n_scored          # peer ratios mostly leave the clip band
     mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    _check_epilogue_all_rows(sp, b, seq_adv, out, st)
     _check_properties(sp, b, out, st, n_scored, mflat)
 
 
-def test_config4_reduced_batch_full_width_sampled():
-    # XGRPO / SGT structure at full V and d with 16 of the 64 prompts (memory-light, same kernels and tiles)
-    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(4, n_prompts=16)
+def test_config4_xgrpo_sgt_full_size_sampled():
+    # XGRPO pooled baseline and SGT auxiliary rows, all 64 prompts
+    mrl, sp, b, seq_adv, out, st, n_scored = _run_full(4)
     assert b["n_aux"] > 0 and st["loss_sgt"] > 0
     mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    _check_epilogue_all_rows(sp, b, seq_adv, out, st)
     _check_properties(sp, b, out, st, n_scored, mflat)
 
 
 def test_config5_full_size_sampled():
     mrl, sp, b, seq_adv, out, st, n_scored = _run_full(5)
     mflat = _check_sampled(sp, b, seq_adv, out, st, n_scored)
+    want = _check_epilogue_all_rows(sp, b, seq_adv, out, st)
+    _check_dw_sampled_vocab_rows(sp, b, out, want["g"])
     _check_properties(sp, b, out, st, n_scored, mflat)
 
 

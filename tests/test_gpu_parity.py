@@ -74,13 +74,7 @@ def _run_both(mrl, synth, sp, chunk_rows=256, dh_dtype=None, logp_tol=util.LOGP_
     logp = got["logp"].cpu().numpy().astype(np.float64)
     assert np.all(logp[~m] == 0.0)
     assert np.max(np.abs(logp[m] - want["logp"][m])) <= logp_tol if m.any() else True
-    # The surrogate sums advantage-signed terms that largely cancel (centred advantages),
-    # so errors are measured against the sum of absolute token terms, not the net value.
-    pg_abs = float(np.sum(want["c"] * np.abs(np.minimum(want["s1"], want["s2"]))))
-    scale = pg_abs + sp.kl_beta * abs(want["loss_kl"]) + sp.sgt_lambda * abs(want["loss_sgt"])
-    for key, sc in (("loss_total", scale), ("loss_pg", pg_abs), ("loss_kl", abs(want["loss_kl"])),
-                    ("loss_sgt", abs(want["loss_sgt"]))):
-        assert abs(st[key] - want[key]) <= rel_tol * max(sc, 1e-12), (key, st[key], want[key], sc)
+    util.check_loss_terms(st, want, sp.kl_beta, sp.sgt_lambda, rel_tol)
     assert st["n_scored_tokens"] == want["n_scored_tokens"]
     assert st["n_clipped_tokens"] == want["n_clipped_tokens"]
     assert st["n_zero_grad_tokens"] == want["n_zero_grad_tokens"]
@@ -91,10 +85,8 @@ def _run_both(mrl, synth, sp, chunk_rows=256, dh_dtype=None, logp_tol=util.LOGP_
 
     dH = util.to_f64(got["dH"])
     assert np.all(dH[~m] == 0.0)
-    e_dh = util.rel_fro(dH, want["dH"])
-    e_dw = util.rel_fro(util.to_f64(got["dW"]), want["dW"])
-    assert e_dh <= rel_tol, ("dH", e_dh)
-    assert e_dw <= rel_tol, ("dW", e_dw)
+    util.check_gradient("dH", dH, want["dH"], rel_tol)
+    util.check_gradient("dW", util.to_f64(got["dW"]), want["dW"], rel_tol)
     return batch, got, want, st
 
 
