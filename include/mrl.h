@@ -54,7 +54,9 @@ typedef enum {
   MRL_ERR_WORKSPACE = -6,        /* workspace NULL, misaligned or too small             */
   MRL_ERR_CONFIG = -7,           /* a configuration value is out of its domain          */
   MRL_ERR_DEVICE = -8,           /* no usable device / a HIP call failed                */
-  MRL_ERR_UNSUPPORTED_ARCH = -9  /* the current device is not gfx950                    */
+  MRL_ERR_UNSUPPORTED_ARCH = -9, /* the current device is not gfx950                    */
+  MRL_ERR_SCRATCH_LIMIT = -10    /* mrl_token_logprobs_static: the input needs more scratch memory
+                                    than the library's built-in buffer holds                      */
 } mrl_status;
 
 typedef enum { MRL_F32 = 0, MRL_BF16 = 1 } mrl_dtype;
@@ -93,6 +95,28 @@ int mrl_token_logprobs(const void* hidden /*[N,d] dev*/, const void* lm_head_w /
                        int64_t N, int32_t d, int32_t V, int32_t dtype,
                        float* out_logp /*[N] dev*/, float* out_lse /*[N] dev | NULL*/,
                        void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
+/* (1c) mrl_token_logprobs for callers that cannot allocate device memory or hand over a
+ *      workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ *      allocation.  Same arguments minus the workspace, same kernels, same results (bit for bit).
+ *      The scratch space is a buffer of MRL_STATIC_SCRATCH_BYTES built into the library's device
+ *      image: every GPU the library runs on holds one copy from the first call until the process
+ *      ends.  The call allocates and frees nothing, on the host side of HIP or the device.
+ *      Limits: the buffer must hold about 8 bytes per row of N plus 16 bytes per vocabulary id
+ *      (the partial sums of the smallest pass, 256 rows); at V = 151936 that allows N up to about
+ *      3.8 million rows.  An input beyond the limit returns MRL_ERR_SCRATCH_LIMIT and launches
+ *      nothing.
+ *      All calls on one GPU share that GPU's buffer: two calls whose work overlaps in time on the
+ *      same GPU (different streams, or different host threads) race on it and give undefined
+ *      results; calls on one stream, or otherwise ordered, are fine.  Nothing in the buffer needs
+ *      to survive between calls and nothing needs clearing: every call writes what it reads. */
+#define MRL_STATIC_SCRATCH_BYTES (32u << 20)
+int mrl_token_logprobs_static(const void* hidden /*[N,d] dev*/, const void* lm_head_w /*[V,d] dev*/,
+                              const int32_t* target_ids /*[N] dev*/,
+                              const uint8_t* token_mask /*[N] dev | NULL*/,
+                              int64_t N, int32_t d, int32_t V, int32_t dtype,
+                              float* out_logp /*[N] dev*/, float* out_lse /*[N] dev | NULL*/,
+                              void* stream);
 
 /* (1b) Scoring pass with diagnostics: the same log-probs plus, when out_entropy is not
  *      NULL, the entropy of the next-token distribution of every scored row,

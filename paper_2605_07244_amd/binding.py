@@ -84,6 +84,9 @@ def lib() -> ctypes.CDLL:
     L.mrl_token_logprobs.restype = c_int
     L.mrl_token_logprobs.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32,
                                      c_int32, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mrl_token_logprobs_static.restype = c_int
+    L.mrl_token_logprobs_static.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32,
+                                            c_int32, c_void_p, c_void_p, c_void_p]
     L.mrl_token_scores_workspace.restype = c_size_t
     L.mrl_token_scores_workspace.argtypes = [c_int64, c_int32, c_int32, c_int32]
     L.mrl_token_scores.restype = c_int
@@ -176,6 +179,22 @@ def token_logprobs(hidden, lm_head_w, target_ids, token_mask=None, workspace=Non
                                   _ptr(out_logp), _ptr(out_lse), _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "mrl_token_logprobs")
     return out_logp, out_lse
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def token_logprobs_static(hidden, lm_head_w, target_ids, token_mask, out_logp, out_lse=None):
+    """mrl_token_logprobs_static: the log-prob call on the library's built-in scratch buffer.  The
+    caller passes the output tensors; nothing is allocated here or in the library."""
+    N, d = hidden.shape
+    V = lm_head_w.shape[0]
+    rc = lib().mrl_token_logprobs_static(_ptr(hidden, name="hidden"), _ptr(lm_head_w, name="lm_head_w"),
+                                         _ptr(target_ids, torch.int32, "target_ids"),
+                                         _ptr(token_mask, torch.uint8, "token_mask"), N, d, V, _dtype_code(hidden),
+                                         _ptr(out_logp, torch.float32, "out_logp"),
+                                         _ptr(out_lse, torch.float32, "out_lse"), _stream())
+    _check(rc, "mrl_token_logprobs_static")
 
 
 def token_scores(hidden, lm_head_w, target_ids, token_mask=None, workspace=None, want_lse=True,

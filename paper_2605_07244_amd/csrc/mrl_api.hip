@@ -7,6 +7,11 @@
 #include <mutex>
 #include <vector>
 
+// Scratch space of mrl_token_logprobs_static.  In host code the array's name is only a handle
+// for the symbol lookup in static_scratch_ptr(), never a device address: every device holds its
+// own copy at its own address, looked up once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[MRL_STATIC_SCRATCH_BYTES];
+
 namespace mrl {
 namespace {
 
@@ -72,6 +77,26 @@ int check_device() {
 }  // namespace
 int require_gfx950() { return check_device(); }
 namespace {
+
+// ------------------------------------------------------------------ built-in scratch buffer
+// Device address of the current device's copy of `scratch`, or nullptr on failure.
+void* static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) { (void)hipGetLastError(); return nullptr; }
+  static std::mutex mu;
+  static std::vector<void*> per_device;
+  std::lock_guard<std::mutex> lk(mu);
+  if ((int)per_device.size() <= dev) per_device.resize(dev + 1, nullptr);
+  if (per_device[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(::scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    per_device[dev] = ptr;
+  }
+  return per_device[dev];
+}
 
 // ------------------------------------------------------------------ workspace layout
 struct Layout {
@@ -231,6 +256,7 @@ const char* mrl_status_string(int status) {
     case MRL_ERR_CONFIG: return "invalid configuration value";
     case MRL_ERR_DEVICE: return "no usable HIP device or a HIP call failed";
     case MRL_ERR_UNSUPPORTED_ARCH: return "device is not gfx950 (no fallback path)";
+    case MRL_ERR_SCRATCH_LIMIT: return "input too large for the library's built-in scratch buffer (use the workspace variant)";
     default: return "unknown status";
   }
 }
@@ -325,6 +351,24 @@ int mrl_token_logprobs(const void* hidden, const void* lm_head_w, const int32_t*
                        void* stream) {
   return mrl_token_scores(hidden, lm_head_w, target_ids, token_mask, N, d, V, dtype, out_logp, out_lse,
                           nullptr, workspace, workspace_bytes, stream);
+}
+
+int mrl_token_logprobs_static(const void* hidden, const void* lm_head_w, const int32_t* target_ids,
+                              const uint8_t* token_mask, int64_t N, int32_t d, int32_t V, int32_t dtype,
+                              float* out_logp, float* out_lse, void* stream) {
+  if (!hidden || !lm_head_w || !target_ids || !out_logp) return MRL_ERR_NULL;
+  int rc = check_common(N, d, V, dtype);
+  if (rc != MRL_OK) return rc;
+  if (N == 0) return MRL_OK;
+  // the size check needs no device: the same rule picks the pass size inside the call below
+  Layout L;
+  if (pick_chunk(N, 0, d, V, dtype, 0, false, MRL_STATIC_SCRATCH_BYTES, L) != MRL_OK) return MRL_ERR_SCRATCH_LIMIT;
+  rc = check_device();
+  if (rc != MRL_OK) return rc;
+  void* ptr = static_scratch_ptr();
+  if (ptr == nullptr) return MRL_ERR_DEVICE;
+  return mrl_token_scores(hidden, lm_head_w, target_ids, token_mask, N, d, V, dtype, out_logp, out_lse,
+                          nullptr, ptr, MRL_STATIC_SCRATCH_BYTES, stream);
 }
 
 // --------------------------------------------------------------------------- (2)

@@ -169,3 +169,17 @@ def test_token_scores_argument_errors():
     assert f(FAKE, FAKE, FAKE, None, 0, 128, 32, 1, FAKE, None, FAKE, None, 0, None) == 0
     # the entropy needs a third partial buffer: its workspace is the larger one
     assert lib.mrl_token_scores_workspace(4096, 256, 4000, 1) > lib.mrl_token_logprobs_workspace(4096, 256, 4000, 1)
+
+
+def test_static_logprobs_argument_errors():
+    """The allocation-free variant validates on the host before it touches a device: NULL
+    pointers, shapes, and inputs beyond its built-in scratch buffer."""
+    f = m.lib().mrl_token_logprobs_static
+    one = 8  # any non-null address: rejected arguments are never dereferenced
+    assert f(None, one, one, None, 16, 128, 512, 1, one, None, None) == -1
+    assert f(one, one, one, None, 16, 100, 512, 1, one, None, None) == -2        # d % 128
+    assert f(one, one, one, None, 16, 128, 512, 7, one, None, None) == -3
+    assert f(one, one, one, None, 0, 128, 512, 1, one, None, None) == 0           # empty input: no-op
+    assert f(one, one, one, None, 1 << 23, 128, 512, 1, one, None, None) == -10   # 8 B per row > 32 MiB
+    assert f(one, one, one, None, 1024, 128, 1 << 22, 1, one, None, None) == -10  # partials of one pass > 32 MiB
+    assert "scratch" in m.status_string(-10)
