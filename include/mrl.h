@@ -196,6 +196,11 @@ int mrl_group_advantages(const float* rewards /*[B] dev*/, const int32_t* group_
  * Every reduction runs in a fixed order (no floating-point atomics): results are
  * bit-reproducible from run to run, so there is no separate deterministic mode.
  * out_dH and/or out_dW may be NULL to skip that gradient.
+ * Numerical range (bf16 path): logits of any offset and scale are handled (exponentials
+ * are taken relative to the row's target logit, in fp32, straight from the accumulators);
+ * the backward operands are exact to bf16 rounding as long as the target's log-prob is
+ * above about -97.  Rows below that are still finite, lose accuracy, and are counted in
+ * n_saturated_rows.
  * ref_logp may be NULL when kl_beta = 0.  group_id[b] must lie in [0, G); a
  * row with an id outside gets weight 0.
  * ---------------------------------------------------------------------- */
@@ -241,6 +246,9 @@ typedef struct {
   int64_t n_zero_grad_tokens;                    /* clipped branch active (no surrogate gradient) */
   int64_t n_bad_targets;                         /* masked-in slots whose target id is outside [0,V) */
   int64_t n_unprocessed_rows;                    /* scored slots beyond scored_rows_hint (0 unless the hint was wrong) */
+  int64_t n_saturated_rows;                      /* bf16 path: scored rows whose target log-prob is below about -97,
+                                                    outside the range the backward operands represent exactly (see
+                                                    "Numerical range" above); their outputs are finite but inexact */
 } mrl_loss_stats;
 
 size_t mrl_grpo_loss_workspace(int64_t B, int32_t T, int32_t d, int32_t V, int32_t dtype,

@@ -61,8 +61,8 @@ class LossConfig:
 
 STATS_FIELDS = ("loss_total", "loss_pg", "loss_kl", "loss_sgt", "mean_ratio", "max_ratio", "mean_k3",
                 "n_scored_tokens", "n_clipped_tokens", "n_zero_grad_tokens", "n_bad_targets",
-                "n_unprocessed_rows")
-STATS_BYTES = 7 * 8 + 5 * 8
+                "n_unprocessed_rows", "n_saturated_rows")
+STATS_BYTES = 7 * 8 + 6 * 8
 
 
 def lib() -> ctypes.CDLL:
@@ -280,7 +280,7 @@ def read_stats(stats: torch.Tensor) -> dict:
     """Copies the device stats block to the host (synchronises) and decodes it."""
     raw = stats.cpu().numpy().tobytes()
     import struct
-    vals = struct.unpack("<7d5q", raw)
+    vals = struct.unpack("<7d6q", raw)
     return dict(zip(STATS_FIELDS, vals))
 
 

@@ -102,9 +102,9 @@ void* static_scratch_ptr() {
 struct Layout {
   size_t total = 0;
   size_t counters, row_index, block_counts, zt, part_max, part_sum, part_ez;
-  size_t seq_len, seq_coef, seq_expo, group_count, lse_c, g_c, loss_partials, Z, Pt, Ht, Wt;
+  size_t seq_len, seq_coef, seq_expo, group_count, lse_c, g_c, row_scale, loss_partials, Z, Pt, Ht, Wt;
   int chunk_rows = 0, n_partials = 0;
-  int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of Z/P and Wt, ldr: of Ht (and the fp32 path's Pt)
+  int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of the stash (Z) and Wt, ldr: of Ht (and the fp32 path's Pt)
   int64_t epi_blocks_total = 0;
 };
 
@@ -134,7 +134,7 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
   L.row_index = take(off, (size_t)(N + 1) * 4);
   L.block_counts = take(off, (size_t)(round_up(2 * nb, 2) * 4 + nb * 8 + 16));
   L.zt = take(off, (size_t)(N + 1) * 4);
-  L.part_max = take(off, (size_t)L.n_partials * chunk_rows * 4);
+  L.part_max = bf16 ? 0 : take(off, (size_t)L.n_partials * chunk_rows * 4);   // fp32 path only
   L.part_sum = take(off, (size_t)L.n_partials * chunk_rows * 4);
   L.part_ez = entropy ? take(off, (size_t)L.n_partials * chunk_rows * 4) : 0;
   if (loss) {
@@ -144,6 +144,7 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
     L.group_count = take(off, (size_t)(B + 1) * 4);
     L.lse_c = take(off, (size_t)(N + 1) * 4);
     L.g_c = take(off, (size_t)(N + 1) * 4);
+    L.row_scale = bf16 ? take(off, (size_t)(N + 1) * 4) : 0;
     L.loss_partials = take(off, (size_t)(L.epi_blocks_total + 1) * 10 * 8);
     L.Z = take(off, (size_t)chunk_rows * L.ldz * es);
     L.Pt = bf16 ? 0 : take(off, (size_t)L.Vp * L.ldr * es);   // fp32 path only: the bf16 dW GEMM reads P itself
@@ -217,7 +218,7 @@ void forward_chunk(const void* H, const void* W, int d, int V, bool bf16, const 
     for (int sub = 0; sub < L.chunk_rows; sub += kFwdSubChunk) {
       const int rows = L.chunk_rows - sub < kFwdSubChunk ? L.chunk_rows - sub : kFwdSubChunk;
       Scope sc(MRL_PROF_GEMM_FWD, s);   // one event pair per kernel launch
-      launch_gemm_fwd_bf16(W, H, row_index, n_scored, c0 + sub, rows, V, d, at<float>(ws, L.part_max) + sub,
+      launch_gemm_fwd_bf16(W, H, row_index, at<float>(ws, L.zt), n_scored, c0 + sub, rows, V, d,
                            at<float>(ws, L.part_sum) + sub, entropy ? at<float>(ws, L.part_ez) + sub : nullptr,
                            L.chunk_rows,
                            stash ? at<uint16_t>(ws, L.Z) + (size_t)sub * L.ldz : nullptr, L.ldz, s);
@@ -335,7 +336,7 @@ int mrl_token_scores(const void* hidden, const void* lm_head_w, const int32_t* t
     forward_chunk(hidden, lm_head_w, d, V, bf16, L, ws, c0, false, s, entropy);
     Scope sc(MRL_PROF_ROW_EPI, s);
     RowEpiArgs e = {};
-    e.part_max = at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
+    e.part_max = bf16 ? nullptr : at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
     e.part_ez = entropy ? at<float>(ws, L.part_ez) : nullptr; e.out_entropy = out_entropy;
     e.n_partials = L.n_partials; e.chunk_rows = L.chunk_rows;
     e.zt = at<float>(ws, L.zt); e.row_index = row_index; e.n_scored = n_scored; e.chunk_start = c0;
@@ -467,7 +468,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
   }
   if (out_dH) {
     Scope sc(MRL_PROF_CONVERT, s);
-    launch_transpose(lm_head_w, d, nullptr, at<void>(ws, L.Wt), L.ldz, V, nullptr, 0, 0, d, L.Vp, es, s);
+    launch_transpose(lm_head_w, d, nullptr, nullptr, at<void>(ws, L.Wt), L.ldz, V, nullptr, 0, 0, d, L.Vp, es, s);
   }
   int64_t n_passes = L.n_chunks;
   if (cfg->scored_rows_hint > 0) {
@@ -483,7 +484,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
       forward_chunk(hidden, lm_head_w, d, V, bf16, L, ws, c0, false, s);
       Scope sc(MRL_PROF_ROW_EPI, s);
       RowEpiArgs e = {};
-      e.part_max = at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
+      e.part_max = bf16 ? nullptr : at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
       e.n_partials = L.n_partials; e.chunk_rows = L.chunk_rows;
       e.zt = at<float>(ws, L.zt); e.row_index = row_index; e.n_scored = n_scored; e.chunk_start = c0;
       e.out_logp = out_logp;
@@ -499,7 +500,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     {
       Scope sc(MRL_PROF_ROW_EPI, s);
       RowEpiArgs e = {};
-      e.part_max = at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
+      e.part_max = bf16 ? nullptr : at<float>(ws, L.part_max); e.part_sum = at<float>(ws, L.part_sum);
       e.n_partials = L.n_partials; e.chunk_rows = L.chunk_rows;
       e.zt = at<float>(ws, L.zt); e.row_index = row_index; e.n_scored = n_scored; e.chunk_start = c0;
       e.behav_logp = behav_logp; e.ref_logp = beta > 0.f ? ref_logp : nullptr; e.seq_adv = seq_adv;
@@ -509,6 +510,10 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
       e.eps_lo = cfg->clip_eps_low; e.eps_hi = cfg->clip_eps_high; e.beta = beta; e.lambda = cfg->sgt_lambda;
       e.out_logp = out_logp; e.out_lse = nullptr;
       e.lse_c = at<float>(ws, L.lse_c); e.g_c = at<float>(ws, L.g_c);
+      if (bf16 && bwd) {
+        e.row_scale = at<float>(ws, L.row_scale); e.estash = at<uint16_t>(ws, L.Z); e.lde = L.ldz;
+        e.targets = target_ids;
+      }
       e.loss_partials = at<double>(ws, L.loss_partials);
       e.partial_block_offset = c * row_epilogue_blocks(L.chunk_rows);
       launch_row_epilogue(e, s);
@@ -516,18 +521,23 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     if (!bwd) continue;
     {
       Scope sc(MRL_PROF_CONVERT, s);
-      launch_convert(at<void>(ws, L.Z), L.ldz, bf16 ? nullptr : at<void>(ws, L.Pt), L.ldr, at<float>(ws, L.lse_c),
-                     at<float>(ws, L.g_c), target_ids, row_index, n_scored, c0, L.chunk_rows, V, (int)L.Vp,
-                     bf16, s);
+      if (bf16) {
+        // the stash already holds the backward operand; only the ragged end of the last pass needs clearing
+        launch_zero_stash_tail(at<void>(ws, L.Z), L.ldz, n_scored, c0, L.chunk_rows, (int)L.Vp, s);
+      } else {
+        launch_convert_f32(at<float>(ws, L.Z), L.ldz, at<float>(ws, L.Pt), L.ldr, at<float>(ws, L.lse_c),
+                           at<float>(ws, L.g_c), target_ids, row_index, n_scored, c0, L.chunk_rows, V, s);
+      }
       if (out_dW)
-        launch_transpose(hidden, d, row_index + c0, at<void>(ws, L.Ht), L.ldr, 0, n_scored, c0,
-                         L.chunk_rows, d, L.chunk_rows, es, s);
+        launch_transpose(hidden, d, row_index + c0, bf16 ? at<float>(ws, L.row_scale) + c0 : nullptr,
+                         at<void>(ws, L.Ht), L.ldr, 0, n_scored, c0, L.chunk_rows, d, L.chunk_rows, es, s);
     }
     if (out_dH) {
       Scope sc(MRL_PROF_GEMM_DH, s);
       if (bf16) {
-        launch_gemm_dh_bf16(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Wt), L.ldz, row_index, n_scored, c0,
-                            L.chunk_rows, (int)L.Vp, d, out_dH, cfg->dh_dtype == MRL_F32, s);
+        launch_gemm_dh_bf16(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Wt), L.ldz, row_index,
+                            at<float>(ws, L.row_scale), n_scored, c0, L.chunk_rows, (int)L.Vp, d, out_dH,
+                            cfg->dh_dtype == MRL_F32, s);
       } else {
         GemmF32Args g = {};
         g.A = at<float>(ws, L.Z); g.lda = L.ldz; g.a_rows = nullptr;

@@ -1,6 +1,6 @@
 // Memory-bound kernels of the scoring path: mask compaction, sequence weights,
-// target logits, partial-merge + token-loss epilogue (Eq. 1 / Eq. 2 terms), the
-// logits -> dz conversion and operand transposes, final reductions.
+// target logits, partial-merge + token-loss epilogue (Eq. 1 / Eq. 2 terms), operand
+// transposes, the fp32 path's logits -> dz conversion, final reductions.
 #include "mrl_internal.h"
 
 namespace mrl {
@@ -349,13 +349,14 @@ __global__ __launch_bounds__(256) void k_row_lse_f32(const float* Z, int64_t ldz
 }
 
 // ----------------------------------------------------------------------------
-// Row epilogue: merge partials -> lse, log-prob; Eq. (1) token terms; loss partials.
+// Row epilogue: merge partials -> lse, log-prob; Eq. (1) token terms; loss partials; for the
+// bf16 backward the row scale -g / S and the patch of the stash's target column.
 // Block = 64 rows x 4 partial lanes.
 // ----------------------------------------------------------------------------
 constexpr int EPI_ROWS = 64;
 constexpr int EPI_NQ = 10;   // doubles per block in loss_partials
 // loss_partials layout per block: 0 pg, 1 kl, 2 sgt, 3 sum_ratio, 4 max_ratio, 5 sum_k3,
-// 6 n_clipped, 7 n_zero_grad, 8 n_grpo_tokens, 9 unused
+// 6 n_clipped, 7 n_zero_grad, 8 n_grpo_tokens, 9 n_saturated_rows
 
 __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
   __shared__ float sh_m[4][EPI_ROWS];
@@ -365,47 +366,58 @@ __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
   const int nvalid = valid_rows(a.n_scored, a.chunk_start, a.chunk_rows);
   const int i = blockIdx.x * EPI_ROWS + tx;           // row within the chunk
   const bool live = i < nvalid;
+  const bool offset_sums = a.part_max == nullptr;     // bf16 kernel: sums of 2^(z log2e - c2)
 
-  float mx = -INFINITY;
-  if (live)
-    for (int p = ty; p < a.n_partials; p += 4) mx = fmaxf(mx, a.part_max[(int64_t)p * a.chunk_rows + i]);
-  sh_m[ty][tx] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(sh_m[0][tx], sh_m[1][tx]), fmaxf(sh_m[2][tx], sh_m[3][tx]));
+  float mx = 0.f;
+  if (!offset_sums) {
+    mx = -INFINITY;
+    if (live)
+      for (int p = ty; p < a.n_partials; p += 4) mx = fmaxf(mx, a.part_max[(int64_t)p * a.chunk_rows + i]);
+    sh_m[ty][tx] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(sh_m[0][tx], sh_m[1][tx]), fmaxf(sh_m[2][tx], sh_m[3][tx]));
+    __syncthreads();
+  }
   float s = 0.f, t = 0.f;
   if (live)
     for (int p = ty; p < a.n_partials; p += 4) {
-      const float pm = a.part_max[(int64_t)p * a.chunk_rows + i];
       const float ps = a.part_sum[(int64_t)p * a.chunk_rows + i];
-      const float sc = pm == -INFINITY ? 0.f : expf(pm - mx);
+      float sc = 1.f;
+      if (!offset_sums) {
+        const float pm = a.part_max[(int64_t)p * a.chunk_rows + i];
+        sc = pm == -INFINITY ? 0.f : expf(pm - mx);
+      }
       s += ps * sc;
       if (a.part_ez != nullptr) t += a.part_ez[(int64_t)p * a.chunk_rows + i] * sc;
     }
   sh_s[ty][tx] = s;
+  sh_m[ty][tx] = t;
   __syncthreads();
-  if (a.part_ez != nullptr) {
-    // entropy H = lse - (sum_v exp(z - max) z) / (sum_v exp(z - max)); sh_m is free again
-    sh_m[ty][tx] = t;
-    __syncthreads();
-    if (ty == 0 && live) {
-      const float ssum = (sh_s[0][tx] + sh_s[1][tx]) + (sh_s[2][tx] + sh_s[3][tx]);
-      const float tsum = (sh_m[0][tx] + sh_m[1][tx]) + (sh_m[2][tx] + sh_m[3][tx]);
-      a.out_entropy[a.row_index[a.chunk_start + i]] = (mx + logf(ssum)) - tsum / ssum;
-    }
-  }
 
   double q[EPI_NQ];
 #pragma unroll
   for (int k = 0; k < EPI_NQ; ++k) q[k] = 0.0;
   if (ty == 0 && live) {
+    constexpr float LOG2E = 1.4426950408889634f;
+    constexpr double LN2 = 0.6931471805599453;
     s = (sh_s[0][tx] + sh_s[1][tx]) + (sh_s[2][tx] + sh_s[3][tx]);
-    const float lse = mx + logf(s);
     const int64_t ci = a.chunk_start + i;
-    const float logp = a.zt[ci] - lse;
+    const float zt = a.zt[ci];
+    // offset sums: lse = (c2 + log2 S) ln 2 with the very c2 the forward kernel subtracted
+    const double lse_d = offset_sums ? ((double)fmaf(zt, LOG2E, kStashMargin2) + log2((double)s)) * LN2
+                                     : (double)mx + log((double)s);
+    const float lse = (float)lse_d;
+    const float logp = (float)((double)zt - lse_d);
     const int64_t slot = a.row_index[ci];
     a.out_logp[slot] = logp;
     if (a.out_lse) a.out_lse[slot] = lse;
     if (a.lse_c) a.lse_c[ci] = lse;
+    if (a.part_ez != nullptr) {
+      // entropy H = lse - (sum_v e z) / (sum_v e)
+      const float tsum = (sh_m[0][tx] + sh_m[1][tx]) + (sh_m[2][tx] + sh_m[3][tx]);
+      a.out_entropy[slot] = (float)(lse_d - (double)tsum / (double)s);
+    }
+    if (offset_sums && logp < kSaturatedLogp) q[9] = 1.0;
     if (a.seq_coef != nullptr) {
       const int64_t b = slot / a.T;
       const float c = a.seq_coef[b];
@@ -443,12 +455,23 @@ __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
         q[2] = -(double)c * (double)logp;
       }
       if (a.g_c) a.g_c[ci] = g;
+      if (a.row_scale) {
+        // dz = g (onehot - e / S) = (-g / S) (e - S onehot): the scale, and the one entry of the
+        // stash row that differs from e
+        a.row_scale[ci] = -g / s;
+        uint16_t* cell = a.estash + (int64_t)i * a.lde + a.targets[slot];
+        const float e_y = __uint_as_float((uint32_t)*cell << 16);
+        const __bf16 patched = (__bf16)(e_y - s);
+        uint16_t bits;
+        __builtin_memcpy(&bits, &patched, 2);
+        *cell = bits;
+      }
     }
   }
   if (a.loss_partials == nullptr) return;
   // fixed-order block reduction of the 64 row threads (ty == 0)
   double* out = a.loss_partials + (a.partial_block_offset + blockIdx.x) * EPI_NQ;
-  for (int k = 0; k < 9; ++k) {
+  for (int k = 0; k < EPI_NQ; ++k) {
     __syncthreads();
     if (ty == 0) sh_q[tx] = q[k];
     __syncthreads();
@@ -470,8 +493,8 @@ __global__ __launch_bounds__(256) void k_finalize(const double* parts, int64_t n
   // rows the enqueued passes did not cover (only when the caller's hint was too small)
   for (int64_t i = rows_enqueued + threadIdx.x; i < *n_scored; i += 256)
     out_logp[row_index[i]] = __builtin_nanf("");
-  __shared__ double tot[9];
-  for (int k = 0; k < 9; ++k) {
+  __shared__ double tot[EPI_NQ];
+  for (int k = 0; k < EPI_NQ; ++k) {
     double acc = 0.0;
     for (int64_t b = threadIdx.x; b < n_blocks; b += 256) {
       const double v = parts[b * EPI_NQ + k];
@@ -503,72 +526,27 @@ __global__ __launch_bounds__(256) void k_finalize(const double* parts, int64_t n
     out_i[2] = (int64_t)(tot[7] + 0.5);
     out_i[3] = *n_bad;
     out_i[4] = *n_scored > rows_enqueued ? *n_scored - rows_enqueued : 0;
+    out_i[5] = (int64_t)(tot[9] + 0.5);
   }
 }
 
 // ----------------------------------------------------------------------------
-// dz conversion, bf16 path (proof of Prop. 4: grad log pi(a_i) = e_i - pi).  Elementwise and
-// in place: fp16 logits z[i][v] -> bf16 P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)).
-// A block converts CV_ROWS rows x 2048 columns, 16 bytes per thread and row.  Rows from the
-// valid count up to its multiple of 128 and columns from V up to Vp are written as zeros
-// (the dW contraction runs over pairs of 64-row panels, the dH one over whole 256-column tiles).
+// bf16 path: rows of the stash from the pass's valid count up to its multiple of 128 are cleared
+// (the dW contraction runs over pairs of 64-row panels and must not meet stale bits there).
 // ----------------------------------------------------------------------------
-constexpr int CV_ROWS = 8, CV_COLS = 2048;
-__global__ __launch_bounds__(256) void k_convert_bf16(uint16_t* ZP, int64_t ldz, const float* lse_c,
-                                                      const float* g_c, const int32_t* targets,
-                                                      const int32_t* row_index, const int64_t* n_scored,
-                                                      int64_t chunk_start, int chunk_rows, int V, int Vp) {
+__global__ __launch_bounds__(256) void k_zero_stash_tail(uint16_t* E, int64_t lde, const int64_t* n_scored,
+                                                         int64_t chunk_start, int chunk_rows, int Vp) {
   const int nvalid = valid_rows(n_scored, chunk_start, chunk_rows);
   const int nzero = (nvalid + 127) / 128 * 128 < chunk_rows ? (nvalid + 127) / 128 * 128 : chunk_rows;
-  const int i0 = blockIdx.y * CV_ROWS;
-  if (i0 >= nzero) return;
-  const int vbase = blockIdx.x * CV_COLS + threadIdx.x * 8;
-  if (vbase >= Vp) return;
-  constexpr float LOG2E = 1.4426950408889634f;
-  uint4 zin[CV_ROWS];
-#pragma unroll
-  for (int k = 0; k < CV_ROWS; ++k) {
-    const int i = i0 + k;
-    zin[k] = make_uint4(0, 0, 0, 0);
-    if (i < nvalid) zin[k] = *reinterpret_cast<const uint4*>(ZP + (int64_t)i * ldz + vbase);
-  }
-#pragma unroll
-  for (int k = 0; k < CV_ROWS; ++k) {
-    const int i = i0 + k;
-    if (i >= nzero) break;
-    uint4 outv = make_uint4(0, 0, 0, 0);
-    if (i < nvalid) {
-      const int64_t ci = chunk_start + i;
-      const float lse2 = lse_c[ci] * LOG2E;
-      const float g = g_c[ci];
-      const int y = targets[row_index[ci]];
-      const uint32_t zw[4] = {zin[k].x, zin[k].y, zin[k].z, zin[k].w};
-      uint32_t ow[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float pv[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const uint16_t hb = (uint16_t)(h ? (zw[q] >> 16) : (zw[q] & 0xffffu));
-          _Float16 hf;
-          __builtin_memcpy(&hf, &hb, 2);
-          const int v = vbase + q * 2 + h;
-          const float p = __builtin_amdgcn_exp2f(fmaf((float)hf, LOG2E, -lse2));
-          const float val = g * ((v == y ? 1.f : 0.f) - p);
-          pv[h] = v < V ? val : 0.f;
-        }
-        const __bf16 b0 = (__bf16)pv[0], b1 = (__bf16)pv[1];
-        uint16_t u0, u1;
-        __builtin_memcpy(&u0, &b0, 2);
-        __builtin_memcpy(&u1, &b1, 2);
-        ow[q] = (uint32_t)u0 | ((uint32_t)u1 << 16);
-      }
-      outv = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-    }
-    *reinterpret_cast<uint4*>(ZP + (int64_t)i * ldz + vbase) = outv;
-  }
+  const int i = nvalid + blockIdx.y;
+  if (i >= nzero) return;
+  const int v = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (v < Vp) *reinterpret_cast<uint4*>(E + (int64_t)i * lde + v) = make_uint4(0, 0, 0, 0);
 }
 
+// ----------------------------------------------------------------------------
+// dz conversion of the fp32 path (proof of Prop. 4: grad log pi(a_i) = e_i - pi).
+// ----------------------------------------------------------------------------
 // fp32 path: scalar, bounds-checked.
 __global__ __launch_bounds__(256) void k_convert_f32(float* ZP, int64_t ldz, float* Pt, int64_t ldpt,
                                                      const float* lse_c, const float* g_c,
@@ -595,6 +573,7 @@ __global__ __launch_bounds__(256) void k_convert_f32(float* ZP, int64_t ldz, flo
 // 2-byte elements, vectorised: tile 64 rows x 64 cols; requires n_cols % 64 == 0,
 // 16-byte aligned rows on both sides and out_cols_pad % 64 == 0.
 __global__ __launch_bounds__(256) void k_transpose_b16(const uint16_t* in, int64_t ld_in, const int32_t* rows,
+                                                       const float* scale /*per row, or nullptr*/,
                                                        uint16_t* out, int64_t ld_out, int64_t n_rows_static,
                                                        const int64_t* n_scored, int64_t chunk_start,
                                                        int chunk_rows) {
@@ -614,6 +593,21 @@ __global__ __launch_bounds__(256) void k_transpose_b16(const uint16_t* in, int64
     if (r < nrows) {
       const int64_t src_row = rows ? (int64_t)rows[r] : r;
       v = *reinterpret_cast<const uint4*>(in + src_row * ld_in + c0 + tc * 8);
+      if (scale != nullptr) {
+        // bf16 elements times the row's scale, rounded back to bf16 (nearest even)
+        const float sc = scale[r];
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const __bf16 lo = (__bf16)(sc * bf16_bits_to_float(w[q] & 0xffffu));
+          const __bf16 hi = (__bf16)(sc * bf16_bits_to_float(w[q] >> 16));
+          uint16_t ul, uh;
+          __builtin_memcpy(&ul, &lo, 2);
+          __builtin_memcpy(&uh, &hi, 2);
+          w[q] = (uint32_t)ul | ((uint32_t)uh << 16);
+        }
+        v = make_uint4(w[0], w[1], w[2], w[3]);
+      }
     }
     *reinterpret_cast<uint4*>(&tile[rr * 72 + tc * 8]) = v;
   }
@@ -726,31 +720,31 @@ void launch_row_epilogue(const RowEpiArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL(k_row_epilogue, dim3(row_epilogue_blocks(a.chunk_rows)), dim3(256), 0, stream, a);
 }
 
-void launch_convert(void* ZP, int64_t ldz, void* Pt, int64_t ldpt, const float* lse_c,
-                    const float* g_c, const int32_t* targets, const int32_t* row_index,
-                    const int64_t* n_scored, int64_t chunk_start, int chunk_rows, int V, int Vp,
-                    int is_bf16, hipStream_t stream) {
-  if (is_bf16) {
-    dim3 grid((Vp + CV_COLS - 1) / CV_COLS, (chunk_rows + CV_ROWS - 1) / CV_ROWS);
-    hipLaunchKernelGGL(k_convert_bf16, grid, dim3(256), 0, stream, static_cast<uint16_t*>(ZP), ldz,
-                       lse_c, g_c, targets, row_index, n_scored, chunk_start, chunk_rows, V, Vp);
-  } else {
-    int gx = (V + 255) / 256; gx = gx > 64 ? 64 : gx;
-    dim3 grid(gx, chunk_rows);
-    hipLaunchKernelGGL(k_convert_f32, grid, dim3(256), 0, stream, static_cast<float*>(ZP), ldz,
-                       static_cast<float*>(Pt), ldpt, lse_c, g_c, targets, row_index, n_scored,
-                       chunk_start, chunk_rows, V);
-  }
+void launch_convert_f32(float* ZP, int64_t ldz, float* Pt, int64_t ldpt, const float* lse_c,
+                        const float* g_c, const int32_t* targets, const int32_t* row_index,
+                        const int64_t* n_scored, int64_t chunk_start, int chunk_rows, int V,
+                        hipStream_t stream) {
+  int gx = (V + 255) / 256; gx = gx > 64 ? 64 : gx;
+  dim3 grid(gx, chunk_rows);
+  hipLaunchKernelGGL(k_convert_f32, grid, dim3(256), 0, stream, ZP, ldz, Pt, ldpt, lse_c, g_c, targets,
+                     row_index, n_scored, chunk_start, chunk_rows, V);
 }
 
-void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, void* out, int64_t ld_out,
+void launch_zero_stash_tail(void* estash, int64_t lde, const int64_t* n_scored, int64_t chunk_start,
+                            int chunk_rows, int Vp, hipStream_t stream) {
+  dim3 grid((Vp / 8 + 255) / 256, 127);
+  hipLaunchKernelGGL(k_zero_stash_tail, grid, dim3(256), 0, stream, static_cast<uint16_t*>(estash), lde,
+                     n_scored, chunk_start, chunk_rows, Vp);
+}
+
+void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, const float* scale, void* out, int64_t ld_out,
                       int64_t n_rows_static, const int64_t* n_scored, int64_t chunk_start,
                       int chunk_rows, int n_cols, int64_t out_cols_pad, int elem_bytes,
                       hipStream_t stream) {
   if (elem_bytes == 2) {
     dim3 grid(n_cols / 64, (unsigned)(out_cols_pad / 64));
     hipLaunchKernelGGL(k_transpose_b16, grid, dim3(256), 0, stream, static_cast<const uint16_t*>(in), ld_in,
-                       rows, static_cast<uint16_t*>(out), ld_out, n_rows_static, n_scored, chunk_start,
+                       rows, scale, static_cast<uint16_t*>(out), ld_out, n_rows_static, n_scored, chunk_start,
                        chunk_rows);
   } else {
     dim3 grid((n_cols + 31) / 32, (unsigned)((out_cols_pad + 31) / 32));

@@ -23,10 +23,12 @@
 //        the M side makes the max / sum-exp reduction over the vocabulary an
 //        in-register reduction with two cross-lane steps.  The fragment rows are
 //        permuted so that a lane's accumulators are 8 consecutive vocabulary ids
-//        and the fp16 logit stash is stored straight from registers.
-//   DH : A = dz rows (tokens), B = W^T;  rows are scattered to the padded slots.
-//   DW : A = dz^T, read from the dz rows themselves (K-major panel, transposing LDS
-//        reads), B = H^T; fp32 read-modify-write of dW.
+//        and the stash of exponentials e = exp(z - row offset) is stored as bf16
+//        straight from registers.
+//   DH : A = stash rows (tokens), B = W^T; each output row is multiplied by its
+//        row scale (-g / S) and scattered to its slot.
+//   DW : A = stash^T, read from the stash rows themselves (K-major panel, transposing
+//        LDS reads), B = (row-scaled H)^T; fp32 read-modify-write of dW.
 #include "mrl_internal.h"
 
 namespace mrl {
@@ -35,17 +37,16 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int NTHREADS = 256;
 constexpr int NSTAGE = 2;                          // LDS double buffer of K panels
 constexpr int TILE_BYTES = BM * BK * 2;            // one operand panel: 32 KB (256 rows x 128 B)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
-constexpr int STASH_LD = BM + 8;                   // fp16 elements per row of the epilogue staging tile
-constexpr int STASH_BYTES = BN * STASH_LD * 2;     // 132 KB
+constexpr int DHSTAGE_LD = BM + 8;                   // bf16 elements per row of the dH epilogue's staging tile
+constexpr int DHSTAGE_BYTES = BN * DHSTAGE_LD * 2;     // 132 KB
 constexpr int PIPE_BYTES = NSTAGE * STAGE_BYTES;   // 128 KB
-constexpr int LDS_BYTES = STASH_BYTES > PIPE_BYTES ? STASH_BYTES : PIPE_BYTES;
+constexpr int LDS_BYTES = DHSTAGE_BYTES > PIPE_BYTES ? DHSTAGE_BYTES : PIPE_BYTES;
 
 // s_waitcnt immediates (gfx9 encoding): wait until at most N vector-memory loads are
 // outstanding, no wait on the export / LDS counters.
@@ -60,9 +61,9 @@ struct Params {
   const int32_t* row_index;   // already offset to the chunk start
   const int64_t* n_scored; int64_t chunk_start; int chunk_rows;
   // FWD
-  float* part_max; float* part_sum; float* part_ez; int64_t part_stride; uint16_t* zstash; int64_t ldz; int V;
+  const float* zt; float* part_sum; float* part_ez; int64_t part_stride; uint16_t* estash; int64_t lde; int V;
   // DH
-  void* dH; int dh_f32; int d;
+  const float* row_scale; void* dH; int dh_f32; int d;
   // DW
   float* dW; int overwrite;
 };
@@ -354,7 +355,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int ncol_base = n0 + wn * 128 + frow;
 
   if (MODE == MODE_FWD) {
-    // rows = vocabulary ids, cols = token rows of the chunk
+    // rows = vocabulary ids, cols = token rows of the chunk.  Exponentials are taken relative to
+    // the row's offset c2 = z_target * log2(e) + margin (log2 domain), one offset for all
+    // vocabulary tiles of a row: e = 2^(z log2(e) - c2), clamped so that neither e nor any sum of
+    // it can overflow.  The sums over the wave's 128 vocabulary ids are this tile's partials; e
+    // itself, as bf16, is the backward pass's operand (dz = (-g / S)(e - S onehot)).
     constexpr float LOG2E = 1.4426950408889634f;
     const bool full = (m0 + BM <= p.V);
     const int pidx = tm * 2 + wm;
@@ -362,86 +367,52 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     auto vrow = [&](int i, int e) {
       return m0 + wm * 128 + 32 * (i >> 1) + 8 * fq + 4 * (i & 1) + e;
     };
+    const bool want_ez = p.part_ez != nullptr;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int n = ncol_base + j * 16;
-      float mx = -INFINITY;
-      if (full) {
+      const bool live = n < N;
+      const float c2 = live ? fmaf(p.zt[n], LOG2E, kStashMargin2) : 0.f;
+      uint16_t* erow = p.estash + (int64_t)n * p.lde + m0 + wm * 128 + 8 * fq;
+      float s = 0.f, t = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+      for (int q = 0; q < 4; ++q) {
+        // accumulators 2q and 2q+1 hold 8 consecutive vocabulary ids of this lane
+        bf16x8 h;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[i][j][e]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) mx = vrow(i, e) < p.V ? fmaxf(mx, acc[i][j][e]) : mx;
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mneg = (mx == -INFINITY) ? 0.f : -mx * LOG2E;
-      float s = 0.f;
-      if (full) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) s += exp2_fast(fmaf(acc[i][j][e], LOG2E, mneg));
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float t = exp2_fast(fmaf(acc[i][j][e], LOG2E, mneg));
-            s += vrow(i, e) < p.V ? t : 0.f;
+            const float z = acc[2 * q + u][j][e];
+            float w = exp2_fast(fminf(fmaf(z, LOG2E, -c2), kStashClamp2));
+            if (!full) w = vrow(2 * q + u, e) < p.V ? w : 0.f;
+            s += w;
+            if (want_ez) t = fmaf(w, z, t);     // for the entropy: sum e * z  (H = lse - E_p[z])
+            h[4 * u + e] = (__bf16)w;
           }
+        if (p.estash != nullptr && live) {
+          // 16 bytes per lane, the four lanes of a token row side by side (64 bytes).  Streaming
+          // store (non-temporal, device scope): the stash is 5 GB per launch and is next read by
+          // the backward launches, so it should not displace operand panels from the L2 and the
+          // memory-side cache (2 % of the launch against a plain store).  Written in assembly
+          // for its cache policy bits; the two wait states after it are the ones the hardware
+          // needs before the data registers of a store wider than 8 bytes may be overwritten
+          // (the compiler inserts them for its own stores only).
+          asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" :: "v"(erow + 32 * q), "v"(h) : "memory");
+        }
       }
       s += __shfl_xor(s, 16);
       s += __shfl_xor(s, 32);
-      if (fq == 0 && n < N) {
-        p.part_max[(int64_t)pidx * p.part_stride + n] = mx;
-        p.part_sum[(int64_t)pidx * p.part_stride + n] = s;
-      }
-      if (p.part_ez != nullptr) {
-        // third partial for the entropy: sum_v exp(z - max) * z  (H = lse - E_p[z])
-        float t = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float z = acc[i][j][e];
-            const float w = exp2_fast(fmaf(z, LOG2E, mneg));
-            t += (full || vrow(i, e) < p.V) ? w * z : 0.f;
-          }
+      if (fq == 0 && live) p.part_sum[(int64_t)pidx * p.part_stride + n] = s;
+      if (want_ez) {
         t += __shfl_xor(t, 16);
         t += __shfl_xor(t, 32);
-        if (fq == 0 && n < N) p.part_ez[(int64_t)pidx * p.part_stride + n] = t;
-      }
-      {
-        // logits as fp16 straight from the accumulators: 8 consecutive vocabulary ids per lane
-        // and store, the four lanes of a token row side by side (64 bytes)
-        if (p.zstash != nullptr && n < N) {
-          uint16_t* zrow = p.zstash + (int64_t)n * p.ldz + m0 + wm * 128 + 8 * fq;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            f16x8 h;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              h[e] = (_Float16)__builtin_amdgcn_fmed3f(acc[2 * t][j][e], -65504.f, 65504.f);
-              h[4 + e] = (_Float16)__builtin_amdgcn_fmed3f(acc[2 * t + 1][j][e], -65504.f, 65504.f);
-            }
-            // streaming store (non-temporal, device scope): the stash is 5 GB per launch and is
-            // next read by the conversion pass, so it should not displace operand panels from the
-            // L2 and the memory-side cache (2 % of the launch against a plain store)
-            // The store is written in assembly for its cache policy bits; the two wait states
-            // after it are the ones the hardware needs before the data registers of a store wider
-            // than 8 bytes may be overwritten (the compiler inserts them for its own stores only).
-            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" :: "v"(zrow + 32 * t), "v"(h) : "memory");
-          }
-        }
+        if (fq == 0 && live) p.part_ez[(int64_t)pidx * p.part_stride + n] = t;
       }
     }
   } else if (MODE == MODE_DH) {
-    // rows = token rows of the chunk (scattered to their slots), cols = hidden index
+    // rows = token rows of the chunk (scattered to their slots), cols = hidden index; a row
+    // of the stash times W is the row's dz W up to its scale -g / S, applied here
     if (p.dh_f32) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
@@ -449,11 +420,12 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
         for (int e = 0; e < 4; ++e) {
           const int m = mrow_base + i * 16 + e;
           if (m < M) {
+            const float sc = p.row_scale[m];
             float* row = reinterpret_cast<float*>(p.dH) + (int64_t)p.row_index[m] * p.d;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
               const int n = ncol_base + j * 16;
-              if (n < p.d) row[n] = acc[i][j][e];
+              if (n < p.d) row[n] = sc * acc[i][j][e];
             }
           }
         }
@@ -463,17 +435,20 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int e = 0; e < 4; ++e) {
+          const int m = mrow_base + i * 16 + e;
+          const float sc = p.row_scale[m < M ? m : M - 1];
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            st[(wm * 128 + i * 16 + 4 * fq + e) * STASH_LD + wn * 128 + j * 16 + frow] = (__bf16)acc[i][j][e];
+          for (int j = 0; j < 8; ++j)
+            st[(wm * 128 + i * 16 + 4 * fq + e) * DHSTAGE_LD + wn * 128 + j * 16 + frow] = (__bf16)(sc * acc[i][j][e]);
+        }
       __syncthreads();
 #pragma unroll 4
       for (int k = 0; k < 32; ++k) {
         const int c = tid + NTHREADS * k;
         const int row = c >> 5, col = c & 31;
         if (m0 + row < M && n0 + col * 8 < p.d) {
-          const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * (STASH_LD * 2) + col * 16);
+          const u32x4 v = *reinterpret_cast<const u32x4*>(smem + row * (DHSTAGE_LD * 2) + col * 16);
           *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.dH) + (int64_t)p.row_index[m0 + row] * p.d + n0 + col * 8) = v;
         }
       }
@@ -523,26 +498,29 @@ void launch(const Params& p, hipStream_t stream) {
 
 }  // namespace
 
-void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index,
+void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index, const float* zt,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                          int V, int d, float* part_max, float* part_sum, float* part_ez,
-                          int64_t part_stride, void* zstash, int64_t ldz, hipStream_t stream) {
+                          int V, int d, float* part_sum, float* part_ez,
+                          int64_t part_stride, void* estash, int64_t lde, hipStream_t stream) {
   Params p = {};
   p.A = static_cast<const uint16_t*>(W); p.lda = d; p.M = V;
   p.B = static_cast<const uint16_t*>(H); p.ldb = d; p.N = chunk_rows;
   p.K = d;
   p.row_index = row_index + chunk_start;
   p.n_scored = n_scored; p.chunk_start = chunk_start; p.chunk_rows = chunk_rows;
-  p.part_max = part_max; p.part_sum = part_sum; p.part_ez = part_ez; p.part_stride = part_stride;
-  p.zstash = static_cast<uint16_t*>(zstash); p.ldz = ldz; p.V = V; p.d = d;
+  p.zt = zt + chunk_start;
+  p.part_sum = part_sum; p.part_ez = part_ez; p.part_stride = part_stride;
+  p.estash = static_cast<uint16_t*>(estash); p.lde = lde; p.V = V; p.d = d;
   launch<MODE_FWD>(p, stream);
 }
 
-void launch_gemm_dh_bf16(const void* P, int64_t ldp, const void* Wt, int64_t ldwt,
-                         const int32_t* row_index, const int64_t* n_scored, int64_t chunk_start,
-                         int chunk_rows, int Vp, int d, void* dH, int dh_f32, hipStream_t stream) {
+void launch_gemm_dh_bf16(const void* E, int64_t lde, const void* Wt, int64_t ldwt,
+                         const int32_t* row_index, const float* row_scale, const int64_t* n_scored,
+                         int64_t chunk_start, int chunk_rows, int Vp, int d, void* dH, int dh_f32,
+                         hipStream_t stream) {
   Params p = {};
-  p.A = static_cast<const uint16_t*>(P); p.lda = ldp; p.M = chunk_rows;
+  p.A = static_cast<const uint16_t*>(E); p.lda = lde; p.M = chunk_rows;
+  p.row_scale = row_scale + chunk_start;
   p.B = static_cast<const uint16_t*>(Wt); p.ldb = ldwt; p.N = d;
   p.K = Vp;
   p.row_index = row_index + chunk_start;
@@ -551,11 +529,11 @@ void launch_gemm_dh_bf16(const void* P, int64_t ldp, const void* Wt, int64_t ldw
   launch<MODE_DH>(p, stream);
 }
 
-void launch_gemm_dw_bf16(const void* P, int64_t ldp, const void* Ht, int64_t ldht,
+void launch_gemm_dw_bf16(const void* E, int64_t lde, const void* Ht, int64_t ldht,
                          const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
                          int V, int d, float* dW, int overwrite, hipStream_t stream) {
   Params p = {};
-  p.A = static_cast<const uint16_t*>(P); p.lda = ldp; p.M = (int)round_up(V, kTile);
+  p.A = static_cast<const uint16_t*>(E); p.lda = lde; p.M = (int)round_up(V, kTile);
   p.B = static_cast<const uint16_t*>(Ht); p.ldb = ldht; p.N = d;
   p.K = chunk_rows;
   p.n_scored = n_scored; p.chunk_start = chunk_start; p.chunk_rows = chunk_rows;

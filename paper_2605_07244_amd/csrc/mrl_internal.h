@@ -27,34 +27,52 @@ struct LdsLimit {
   }
 };
 
-// Number of (max, sum-exp) partials each token row receives from the forward
-// kernel: the bf16 kernel emits two per 256-wide vocabulary tile (one per wave
-// row), the fp32 path a single one per row.
+// Number of sum-exp partials each token row receives from the forward kernel: the bf16
+// kernel emits two per 256-wide vocabulary tile (one per wave row), the fp32 path a single
+// (max, sum-exp) pair per row.
 inline int fwd_partials_bf16(int V) { return 2 * (int)((V + kTile - 1) / kTile); }
+
+// bf16 path: exponentials are taken relative to a per-row offset that is known before the forward
+// launch, c2[n] = z_t[n] * log2(e) + kStashMargin2 (log2 domain, z_t = the row's target logit):
+//   e[n, v] = 2^(min(z[n, v] * log2(e) - c2[n], kStashClamp2)),   S[n] = sum_v e[n, v].
+// One offset for the whole row is what lets the forward kernel write e itself (as bf16) for the
+// backward pass: softmax = e / S, so dz = g (onehot - e / S) = (-g / S) (e - S onehot) is the
+// stored row, patched at the target column, times a per-row scalar that the dH epilogue applies
+// to its output rows and that the dW launch finds folded into its copy of the hidden rows.
+// Relative to the target logit nothing of weight can underflow (e >= p * 2^-margin) and the
+// largest entry is exp(-logp_target) * 2^-margin.  With margin 60 and clamp 100 every quantity
+// stays a normal bf16 / fp32 number for log-probs of the target down to about -97; below that
+// the row saturates (finite, inexact) and is counted.
+constexpr float kStashMargin2 = 60.f;
+constexpr float kStashClamp2 = 100.f;
+constexpr float kSaturatedLogp = -97.f;
 
 // ---- bf16 MFMA GEMM family: C[m][n] = sum_k A[m][k] * B[n][k] ---------------
 // n_scored: device pointer to the number of compacted rows; chunk_start/chunk_rows
 // select the rows this launch covers (valid rows = clamp(n_scored - chunk_start, 0, chunk_rows)).
 
-// Forward: A = W [V, d], B = H rows gathered through row_index[chunk_start + n].
-// Writes per-row partials part_max/part_sum[(2*tile_m + wave_m) * part_stride + n]
-// (max and sum exp(z - max) over the partial's 128 vocabulary rows), when part_ez != nullptr also
-// sum exp(z - max) * z (for the entropy), and, when zstash != nullptr, the logits as fp16 into
-// zstash[n * ldz + v] (n = row within this launch).
-void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index,
+// Forward: A = W [V, d], B = H rows gathered through row_index[chunk_start + n]; zt[chunk_start + n]
+// is the row's target logit.  Writes per-row partials part_sum[(2*tile_m + wave_m) * part_stride + n]
+// = sum of e[n, v] over the partial's 128 vocabulary rows (e as defined above), when part_ez != nullptr
+// also sum e * z (for the entropy), and, when estash != nullptr, e itself as bf16 into
+// estash[n * lde + v] (n = row within this launch; columns V .. round_up(V, 256) get zeros).
+void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index, const float* zt,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                          int V, int d, float* part_max, float* part_sum, float* part_ez,
-                          int64_t part_stride, void* zstash, int64_t ldz, hipStream_t stream);
+                          int V, int d, float* part_sum, float* part_ez,
+                          int64_t part_stride, void* estash, int64_t lde, hipStream_t stream);
 
-// dH: A = P [chunk_rows, Vp] (bf16 dz), B = Wt [d, Vp]; row m goes to
-// dH[row_index[chunk_start + m], :] as bf16 (dh_f32 = 0) or float (dh_f32 = 1).
-void launch_gemm_dh_bf16(const void* P, int64_t ldp, const void* Wt, int64_t ldwt,
-                         const int32_t* row_index, const int64_t* n_scored, int64_t chunk_start,
-                         int chunk_rows, int Vp, int d, void* dH, int dh_f32, hipStream_t stream);
+// dH: A = E [chunk_rows, Vp] (the patched bf16 stash), B = Wt [d, Vp]; row m, multiplied by
+// row_scale[chunk_start + m], goes to dH[row_index[chunk_start + m], :] as bf16 (dh_f32 = 0) or
+// float (dh_f32 = 1).
+void launch_gemm_dh_bf16(const void* E, int64_t lde, const void* Wt, int64_t ldwt,
+                         const int32_t* row_index, const float* row_scale, const int64_t* n_scored,
+                         int64_t chunk_start, int chunk_rows, int Vp, int d, void* dH, int dh_f32,
+                         hipStream_t stream);
 
-// dW: A = P^T read in place from P [chunk_rows, Vp] (rows >= valid rows rounded up to 128 and
-// columns >= V must be zero), B = Ht [d, chunk_rows]; dW[v, :] = (or +=) sum over the
-// chunk's valid rows.  overwrite = 1 stores, 0 adds into the existing values.
+// dW: A = E^T read in place from E [chunk_rows, Vp] (rows >= valid rows rounded up to 128 and
+// columns >= V must be zero), B = Ht [d, chunk_rows] (the pass's hidden rows, each already
+// multiplied by its row scale); dW[v, :] = (or +=) sum over the chunk's valid rows.
+// overwrite = 1 stores, 0 adds into the existing values.
 void launch_gemm_dw_bf16(const void* P, int64_t ldp, const void* Ht, int64_t ldht,
                          const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
                          int V, int d, float* dW, int overwrite, hipStream_t stream);
@@ -117,6 +135,8 @@ void launch_row_lse_f32(const float* Z, int64_t ldz, const int64_t* n_scored, in
                         hipStream_t stream);
 
 struct RowEpiArgs {
+  // part_max == nullptr: part_sum holds the bf16 kernel's offset sums (see kStashMargin2);
+  // else (fp32 path) one (max, sum exp(z - max)) pair per row
   const float* part_max; const float* part_sum; int n_partials; int chunk_rows;
   const float* part_ez; float* out_entropy;   // both nullptr unless the entropy is asked for (per slot)
   const float* zt;            // [N] compacted
@@ -129,24 +149,30 @@ struct RowEpiArgs {
   float eps_lo, eps_hi, beta, lambda;
   float* out_logp; float* out_lse;  // per slot
   float* lse_c; float* g_c;         // per compacted row (nullptr to skip)
+  // bf16 backward: row_scale[ci] = -g / S, and the stash row's target column becomes e - S
+  float* row_scale; uint16_t* estash; int64_t lde; const int32_t* targets;
   double* loss_partials;            // [n_blocks_total][8], block index = chunk block offset + blockIdx
   int64_t partial_block_offset;
 };
 int row_epilogue_blocks(int chunk_rows);
 void launch_row_epilogue(const RowEpiArgs& a, hipStream_t stream);
 
-// dz conversion: reads the chunk's logits (fp16 for the bf16 path, float for fp32),
-// writes P[i][v] = g_i (1[v = y_i] - exp(z - lse_i)) in place (same element size); rows from
-// the valid count up to its multiple of 128 and columns >= V become zero.  The fp32 path also
-// writes the transpose Pt[v][i] (Pt is unused, and may be null, for bf16).
-void launch_convert(void* ZP, int64_t ldz, void* Pt, int64_t ldpt, const float* lse_c,
-                    const float* g_c, const int32_t* targets, const int32_t* row_index,
-                    const int64_t* n_scored, int64_t chunk_start, int chunk_rows, int V, int Vp,
-                    int is_bf16, hipStream_t stream);
+// fp32 path, dz conversion: reads the chunk's float logits, writes P[i][v] = g_i (1[v = y_i] -
+// exp(z - lse_i)) in place and its transpose Pt[v][i].
+void launch_convert_f32(float* ZP, int64_t ldz, float* Pt, int64_t ldpt, const float* lse_c,
+                        const float* g_c, const int32_t* targets, const int32_t* row_index,
+                        const int64_t* n_scored, int64_t chunk_start, int chunk_rows, int V,
+                        hipStream_t stream);
 
-// Out[c][r] = In[rows[r]][c] (rows == nullptr: identity) for r < n_rows_valid, zero beyond,
-// r in [0, out_cols_pad), c in [0, n_cols).  Used for Wt (static) and Ht (gathered, dynamic).
-void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, void* out, int64_t ld_out,
+// bf16 path: zeroes the stash rows from the pass's valid count up to its multiple of 128 (the dW
+// contraction runs over pairs of 64-row panels; the forward kernel writes valid rows only).
+void launch_zero_stash_tail(void* estash, int64_t lde, const int64_t* n_scored, int64_t chunk_start,
+                            int chunk_rows, int Vp, hipStream_t stream);
+
+// Out[c][r] = scale[r] * In[rows[r]][c] (rows == nullptr: identity; scale == nullptr: 1, 2-byte
+// elements only) for r < n_rows_valid, zero beyond, r in [0, out_cols_pad), c in [0, n_cols).
+// Used for Wt (static) and Ht (gathered, dynamic, scaled).
+void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, const float* scale, void* out, int64_t ld_out,
                       int64_t n_rows_static, const int64_t* n_scored, int64_t chunk_start,
                       int chunk_rows, int n_cols, int64_t out_cols_pad, int elem_bytes,
                       hipStream_t stream);

@@ -35,8 +35,8 @@ def test_version_and_status_strings():
 
 
 def test_stats_struct_size_matches_header():
-    # 7 doubles + 5 int64 (see mrl_loss_stats)
-    assert binding.STATS_BYTES == 96 and len(binding.STATS_FIELDS) == 12
+    # 7 doubles + 6 int64 (see mrl_loss_stats)
+    assert binding.STATS_BYTES == 104 and len(binding.STATS_FIELDS) == 13
 
 
 P = ctypes.c_void_p
