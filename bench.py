@@ -120,6 +120,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-rows", type=int, default=0)
     ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (debug)")
+    ap.add_argument("--hidden", type=int, default=0, help="override the hidden width d (debug)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the legs that are not part of `value` (alignment pass, forward-only scoring pass); "
                          "used for kernel profiles so that only the step's launches are in the trace")
@@ -143,6 +144,8 @@ def main():
         over["len_dist"] = "full"
     if args.prompts:
         over["n_prompts"] = args.prompts
+    if args.hidden:
+        over["d"] = args.hidden
     sp = synth.spec(args.config, **over)
     log(f"generating workload {sp.name}: V={sp.V} d={sp.d} prompts={sp.n_prompts} T={sp.T}")
     batch = synth.make(sp, "cuda")

@@ -29,7 +29,9 @@
  *     between inputs and labels is the caller's business.  No bias, sampling
  *     temperature 1.
  *   - dtype MRL_BF16: hidden / lm_head_w are bfloat16, matrix products run on
- *     the bf16 MFMA units with fp32 accumulation; d must be a multiple of 128 (the K loop of the GEMM kernels runs over pairs of 64-wide panels).
+ *     the bf16 MFMA units with fp32 accumulation; d must be a multiple of 8 (rows of 16-byte
+ *     vectors).  Widths that are not a multiple of 128 run on zero-padded copies of the operands
+ *     (a little extra workspace and time); multiples of 256 use the matrix cores best.
  *     dtype MRL_F32: hidden / lm_head_w are float, plain fp32 arithmetic (a
  *     small-shape sanity path, not tuned); any d >= 1.
  *   - Only gfx950 devices are supported; there is no fallback path.
@@ -199,7 +201,9 @@ int mrl_group_advantages(const float* rewards /*[B] dev*/, const int32_t* group_
  * Numerical range (bf16 path): logits of any offset and scale are handled (exponentials
  * are taken relative to the row's target logit, in fp32, straight from the accumulators);
  * the backward operands are exact to bf16 rounding as long as the target's log-prob is
- * above about -97.  Rows below that are still finite, lose accuracy, and are counted in
+ * above about -97.  A row below that (a token the learner deems impossible, p < 1e-42)
+ * reports a finite, saturated log-prob <= -97, contributes nothing to the loss and the
+ * gradients (it still counts in its sequence's length), and is counted in
  * n_saturated_rows.
  * ref_logp may be NULL when kl_beta = 0.  group_id[b] must lie in [0, G); a
  * row with an id outside gets weight 0.
@@ -247,8 +251,8 @@ typedef struct {
   int64_t n_bad_targets;                         /* masked-in slots whose target id is outside [0,V) */
   int64_t n_unprocessed_rows;                    /* scored slots beyond scored_rows_hint (0 unless the hint was wrong) */
   int64_t n_saturated_rows;                      /* bf16 path: scored rows whose target log-prob is below about -97,
-                                                    outside the range the backward operands represent exactly (see
-                                                    "Numerical range" above); their outputs are finite but inexact */
+                                                    outside the range the backward operands represent (see
+                                                    "Numerical range" above): dropped from the loss and the gradients */
 } mrl_loss_stats;
 
 size_t mrl_grpo_loss_workspace(int64_t B, int32_t T, int32_t d, int32_t V, int32_t dtype,

@@ -103,6 +103,9 @@ struct Layout {
   size_t total = 0;
   size_t counters, row_index, block_counts, zt, part_max, part_sum, part_ez;
   size_t seq_len, seq_coef, seq_expo, group_count, lse_c, g_c, row_scale, loss_partials, Z, Pt, Ht, Wt;
+  size_t Hc = 0, Wp = 0;       // bf16: the pass's token rows, gathered and zero-padded to dp columns; W padded likewise (only if dp != d)
+  int dp = 0;                  // bf16: d rounded up to the 128-wide panel pairs of the GEMM kernels
+  int64_t ldh = 0;             // row stride of Hc and Wp
   int chunk_rows = 0, n_partials = 0;
   int64_t n_chunks = 0, Vp = 0, ldz = 0, ldr = 0;   // ldz: row stride of the stash (Z) and Wt, ldr: of Ht (and the fp32 path's Pt)
   int64_t epi_blocks_total = 0;
@@ -137,6 +140,13 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
   L.part_max = bf16 ? 0 : take(off, (size_t)L.n_partials * chunk_rows * 4);   // fp32 path only
   L.part_sum = take(off, (size_t)L.n_partials * chunk_rows * 4);
   L.part_ez = entropy ? take(off, (size_t)L.n_partials * chunk_rows * 4) : 0;
+  const int dk = bf16 ? (int)round_up(d, 128) : d;   // rows of Ht / Wt
+  if (bf16) {
+    L.dp = dk;
+    L.ldh = L.dp + 64;
+    L.Hc = take(off, (size_t)chunk_rows * L.ldh * 2);
+    if (L.dp != d) L.Wp = take(off, (size_t)V * L.ldh * 2);
+  }
   if (loss) {
     L.seq_len = take(off, (size_t)(B + 1) * 4);
     L.seq_coef = take(off, (size_t)(B + 1) * 4);
@@ -148,8 +158,8 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
     L.loss_partials = take(off, (size_t)(L.epi_blocks_total + 1) * 10 * 8);
     L.Z = take(off, (size_t)chunk_rows * L.ldz * es);
     L.Pt = bf16 ? 0 : take(off, (size_t)L.Vp * L.ldr * es);   // fp32 path only: the bf16 dW GEMM reads P itself
-    L.Ht = take(off, (size_t)d * L.ldr * es);
-    L.Wt = take(off, (size_t)d * L.ldz * es);
+    L.Ht = take(off, (size_t)dk * L.ldr * es);
+    L.Wt = take(off, (size_t)dk * L.ldz * es);
   } else if (!bf16) {
     L.Z = take(off, (size_t)chunk_rows * L.ldz * es);
   }
@@ -166,7 +176,7 @@ int default_chunk(int64_t N, int dtype) {
 int check_common(int64_t N, int d, int V, int dtype) {
   if (dtype != MRL_F32 && dtype != MRL_BF16) return MRL_ERR_DTYPE;
   if (N < 0 || N > kMaxSlots || d <= 0 || V <= 0) return MRL_ERR_SHAPE;
-  if (dtype == MRL_BF16 && d % 128 != 0) return MRL_ERR_SHAPE;
+  if (dtype == MRL_BF16 && d % 8 != 0) return MRL_ERR_SHAPE;   // 16-byte rows
   if ((int64_t)V > ((int64_t)1 << 24) || d > (1 << 20)) return MRL_ERR_SHAPE;
   return MRL_OK;
 }
@@ -215,10 +225,17 @@ void forward_chunk(const void* H, const void* W, int d, int V, bool bf16, const 
   const int32_t* row_index = at<int32_t>(ws, L.row_index);
   const int64_t* n_scored = at<int64_t>(ws, L.counters);
   if (bf16) {
+    {
+      Scope sc(MRL_PROF_CONVERT, s);
+      launch_gather_rows_b16(H, d, row_index + c0, at<void>(ws, L.Hc), L.ldh, 0, n_scored, c0, L.chunk_rows, d, L.dp, s);
+    }
+    const void* Wk = L.dp != d ? at<void>(ws, L.Wp) : W;
+    const int64_t ldw = L.dp != d ? L.ldh : d;
     for (int sub = 0; sub < L.chunk_rows; sub += kFwdSubChunk) {
       const int rows = L.chunk_rows - sub < kFwdSubChunk ? L.chunk_rows - sub : kFwdSubChunk;
       Scope sc(MRL_PROF_GEMM_FWD, s);   // one event pair per kernel launch
-      launch_gemm_fwd_bf16(W, H, row_index, at<float>(ws, L.zt), n_scored, c0 + sub, rows, V, d,
+      launch_gemm_fwd_bf16(Wk, ldw, at<uint16_t>(ws, L.Hc) + (size_t)sub * L.ldh, L.ldh, L.dp, at<float>(ws, L.zt),
+                           n_scored, c0 + sub, rows, V, d,
                            at<float>(ws, L.part_sum) + sub, entropy ? at<float>(ws, L.part_ez) + sub : nullptr,
                            L.chunk_rows,
                            stash ? at<uint16_t>(ws, L.Z) + (size_t)sub * L.ldz : nullptr, L.ldz, s);
@@ -249,7 +266,7 @@ const char* mrl_status_string(int status) {
   switch (status) {
     case MRL_OK: return "ok";
     case MRL_ERR_NULL: return "a required pointer is NULL";
-    case MRL_ERR_SHAPE: return "invalid shape (sizes must be positive; bf16 needs d % 128 == 0)";
+    case MRL_ERR_SHAPE: return "invalid shape (sizes must be positive; bf16 needs d % 8 == 0)";
     case MRL_ERR_DTYPE: return "unknown dtype";
     case MRL_ERR_TARGET_RANGE: return "target id out of range";
     case MRL_ERR_GROUP_RANGE: return "group id out of range";
@@ -330,6 +347,7 @@ int mrl_token_scores(const void* hidden, const void* lm_head_w, const int32_t* t
     launch_zero_unscored(token_mask, target_ids, N, V, d, out_logp, out_lse, nullptr, 0, s);
     if (entropy) launch_zero_unscored(token_mask, target_ids, N, V, d, out_entropy, nullptr, nullptr, 0, s);
     launch_target_logit(hidden, lm_head_w, target_ids, row_index, n_scored, N, d, bf16, at<float>(ws, L.zt), s);
+    if (L.Wp != 0) launch_gather_rows_b16(lm_head_w, d, nullptr, at<void>(ws, L.Wp), L.ldh, V, nullptr, 0, 0, d, L.dp, s);
   }
   for (int64_t c = 0; c < L.n_chunks; ++c) {
     const int64_t c0 = c * L.chunk_rows;
@@ -453,6 +471,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
     launch_zero_unscored(token_mask, target_ids, N, V, d, out_logp, nullptr, out_dH,
                          cfg->dh_dtype == MRL_BF16 ? 2 : 4, s);
     launch_target_logit(hidden, lm_head_w, target_ids, row_index, n_scored, N, d, bf16, at<float>(ws, L.zt), s);
+    if (L.Wp != 0) launch_gather_rows_b16(lm_head_w, d, nullptr, at<void>(ws, L.Wp), L.ldh, V, nullptr, 0, 0, d, L.dp, s);
   }
   if (cfg->debug_sync) {
     // debugging aid: wait for the preparation kernels and turn the device-side range counters
@@ -468,7 +487,11 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
   }
   if (out_dH) {
     Scope sc(MRL_PROF_CONVERT, s);
-    launch_transpose(lm_head_w, d, nullptr, nullptr, at<void>(ws, L.Wt), L.ldz, V, nullptr, 0, 0, d, L.Vp, es, s);
+    if (bf16)
+      launch_transpose(L.Wp != 0 ? at<void>(ws, L.Wp) : lm_head_w, L.Wp != 0 ? L.ldh : d, nullptr, nullptr,
+                       at<void>(ws, L.Wt), L.ldz, V, nullptr, 0, 0, L.dp, L.Vp, es, s);
+    else
+      launch_transpose(lm_head_w, d, nullptr, nullptr, at<void>(ws, L.Wt), L.ldz, V, nullptr, 0, 0, d, L.Vp, es, s);
   }
   int64_t n_passes = L.n_chunks;
   if (cfg->scored_rows_hint > 0) {
@@ -528,9 +551,12 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
         launch_convert_f32(at<float>(ws, L.Z), L.ldz, at<float>(ws, L.Pt), L.ldr, at<float>(ws, L.lse_c),
                            at<float>(ws, L.g_c), target_ids, row_index, n_scored, c0, L.chunk_rows, V, s);
       }
-      if (out_dW)
-        launch_transpose(hidden, d, row_index + c0, bf16 ? at<float>(ws, L.row_scale) + c0 : nullptr,
-                         at<void>(ws, L.Ht), L.ldr, 0, n_scored, c0, L.chunk_rows, d, L.chunk_rows, es, s);
+      if (out_dW && bf16)   // from the pass's gathered rows, each times its row scale
+        launch_transpose(at<void>(ws, L.Hc), L.ldh, nullptr, at<float>(ws, L.row_scale) + c0, at<void>(ws, L.Ht), L.ldr,
+                         0, n_scored, c0, L.chunk_rows, L.dp, L.chunk_rows, es, s);
+      else if (out_dW)
+        launch_transpose(hidden, d, row_index + c0, nullptr, at<void>(ws, L.Ht), L.ldr, 0, n_scored, c0,
+                         L.chunk_rows, d, L.chunk_rows, es, s);
     }
     if (out_dH) {
       Scope sc(MRL_PROF_GEMM_DH, s);

@@ -417,8 +417,16 @@ __global__ __launch_bounds__(256) void k_row_epilogue(RowEpiArgs a) {
       const float tsum = (sh_m[0][tx] + sh_m[1][tx]) + (sh_m[2][tx] + sh_m[3][tx]);
       a.out_entropy[slot] = (float)(lse_d - (double)tsum / (double)s);
     }
-    if (offset_sums && logp < kSaturatedLogp) q[9] = 1.0;
-    if (a.seq_coef != nullptr) {
+    // A target log-prob below the range the bf16 backward operands represent (only possible for a
+    // token the learner deems impossible): the row is counted and dropped from the loss and the
+    // gradients (weight 0), as a row with an invalid target would be.
+    const bool saturated = offset_sums && logp < kSaturatedLogp;
+    if (saturated) {
+      q[9] = 1.0;
+      if (a.g_c) a.g_c[ci] = 0.f;
+      if (a.row_scale) a.row_scale[ci] = 0.f;
+    }
+    if (a.seq_coef != nullptr && !saturated) {
       const int64_t b = slot / a.T;
       const float c = a.seq_coef[b];
       const int kind = a.seq_kind ? a.seq_kind[b] : 0;
@@ -564,6 +572,31 @@ __global__ __launch_bounds__(256) void k_convert_f32(float* ZP, int64_t ldz, flo
     const float val = g * ((v == y ? 1.f : 0.f) - p);
     ZP[(int64_t)i * ldz + v] = val;
     Pt[(int64_t)v * ldpt + i] = val;
+  }
+}
+
+// ----------------------------------------------------------------------------
+// Row gather with zero padding: Out[r][0:dp] = In[rows[r]][0:d] | 0.  Makes the forward launch's
+// token-row operand contiguous (no index lookups in the kernel) and its K extent a multiple of
+// the kernel's 128-wide panel pairs; the same routine pads W when d is not such a multiple.
+// ----------------------------------------------------------------------------
+constexpr int GATHER_ROWS = 4;
+__global__ __launch_bounds__(256) void k_gather_rows_b16(const uint16_t* in, int64_t ld_in, const int32_t* rows,
+                                                         uint16_t* out, int64_t ld_out, int64_t n_rows_static,
+                                                         const int64_t* n_scored, int64_t chunk_start,
+                                                         int chunk_rows, int d, int dp) {
+  int64_t nrows = n_rows_static;
+  if (n_scored != nullptr) nrows = valid_rows(n_scored, chunk_start, chunk_rows);
+#pragma unroll
+  for (int k = 0; k < GATHER_ROWS; ++k) {
+    const int64_t r = (int64_t)blockIdx.x * GATHER_ROWS + k;
+    if (r >= nrows) return;
+    const int64_t src = rows ? (int64_t)rows[r] : r;
+    for (int c = threadIdx.x * 8; c < dp; c += 256 * 8) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (c < d) v = *reinterpret_cast<const uint4*>(in + src * ld_in + c);
+      *reinterpret_cast<uint4*>(out + r * ld_out + c) = v;
+    }
   }
 }
 
@@ -735,6 +768,16 @@ void launch_zero_stash_tail(void* estash, int64_t lde, const int64_t* n_scored, 
   dim3 grid((Vp / 8 + 255) / 256, 127);
   hipLaunchKernelGGL(k_zero_stash_tail, grid, dim3(256), 0, stream, static_cast<uint16_t*>(estash), lde,
                      n_scored, chunk_start, chunk_rows, Vp);
+}
+
+void launch_gather_rows_b16(const void* in, int64_t ld_in, const int32_t* rows, void* out, int64_t ld_out,
+                            int64_t n_rows_static, const int64_t* n_scored, int64_t chunk_start,
+                            int chunk_rows, int d, int dp, hipStream_t stream) {
+  const int64_t max_rows = n_scored != nullptr ? chunk_rows : n_rows_static;
+  if (max_rows <= 0) return;
+  hipLaunchKernelGGL(k_gather_rows_b16, dim3((unsigned)((max_rows + GATHER_ROWS - 1) / GATHER_ROWS)), dim3(256), 0,
+                     stream, static_cast<const uint16_t*>(in), ld_in, rows, static_cast<uint16_t*>(out), ld_out,
+                     n_rows_static, n_scored, chunk_start, chunk_rows, d, dp);
 }
 
 void launch_transpose(const void* in, int64_t ld_in, const int32_t* rows, const float* scale, void* out, int64_t ld_out,

@@ -46,7 +46,10 @@ constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
 constexpr int DHSTAGE_LD = BM + 8;                   // bf16 elements per row of the dH epilogue's staging tile
 constexpr int DHSTAGE_BYTES = BN * DHSTAGE_LD * 2;     // 132 KB
 constexpr int PIPE_BYTES = NSTAGE * STAGE_BYTES;   // 128 KB
-constexpr int LDS_BYTES = DHSTAGE_BYTES > PIPE_BYTES ? DHSTAGE_BYTES : PIPE_BYTES;
+constexpr int ZT_BYTES = BN * 4;                   // forward: the tile's 256 target logits, behind the panels
+template <int MODE> constexpr int lds_bytes() {
+  return MODE == 0 ? PIPE_BYTES + ZT_BYTES : (DHSTAGE_BYTES > PIPE_BYTES ? DHSTAGE_BYTES : PIPE_BYTES);
+}
 
 // s_waitcnt immediates (gfx9 encoding): wait until at most N vector-memory loads are
 // outstanding, no wait on the export / LDS counters.
@@ -60,6 +63,7 @@ struct Params {
   int K;
   const int32_t* row_index;   // already offset to the chunk start
   const int64_t* n_scored; int64_t chunk_start; int chunk_rows;
+  int sup_m, sup_n;           // super-tile shape of the workgroup -> tile mapping
   // FWD
   const float* zt; float* part_sum; float* part_ez; int64_t part_stride; uint16_t* estash; int64_t lde; int V;
   // DH
@@ -68,24 +72,36 @@ struct Params {
   float* dW; int overwrite;
 };
 
-// Workgroup -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs,
-// each with its own L2; 32 consecutive workgroups of one XCD form an 8 x 4
-// super-tile so that they share operand panels in that L2, and super-tiles are
-// numbered N-fastest so that the XCDs walk the same A rows at the same time.
-constexpr int SUP_M = 8, SUP_N = 4, NXCD = 8;
-__host__ __device__ inline int num_blocks(int Mt, int Nt) {
-  int s = ((Mt + SUP_M - 1) / SUP_M) * ((Nt + SUP_N - 1) / SUP_N);
-  return (s + NXCD - 1) / NXCD * NXCD * (SUP_M * SUP_N);
+// Workgroup -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs, each with its own
+// L2 and 32 compute units; sup_m x sup_n consecutive workgroups of one XCD form a super-tile so
+// that they share operand panels in that L2 (each A panel is used by sup_n tiles, each B panel by
+// sup_m), and super-tiles are numbered N-fastest so that the XCDs walk the same A rows at the same
+// time.  The shape is picked per launch from what measurement favours: 8 x 4 when the N extent is
+// a multiple of 4 tiles, else 8 x 2.  Two things matter more than the panel-sharing count: the N
+// extent must fill whole super-tile columns (6 tiles at d = 1536 and 14 at d = 3584 leave 8 x 4
+// with a half-empty last column: dH / dW 11-30 % slower than 8 x 2), and the super-tile size
+// must divide the 32 compute units of an XCD, so that the workgroups running on it at any time
+// are whole super-tiles (shapes of 24, 28 or 30 tiles lose 5-20 %).
+constexpr int NXCD = 8;
+struct SuperTile { int m, n; };
+inline SuperTile pick_super_tile(int Nt) {
+  if (Nt % 4 == 0) return {8, 4};
+  if (Nt == 1) return {16, 1};
+  return {8, 2};
 }
-__device__ inline bool tile_coords(int bid, int Mt, int Nt, int& tm, int& tn, int& sm, int& sn) {
-  const int sNt = (Nt + SUP_N - 1) / SUP_N, sMt = (Mt + SUP_M - 1) / SUP_M;
+__host__ __device__ inline int num_blocks(int Mt, int Nt, int sup_m, int sup_n) {
+  int s = ((Mt + sup_m - 1) / sup_m) * ((Nt + sup_n - 1) / sup_n);
+  return (s + NXCD - 1) / NXCD * NXCD * (sup_m * sup_n);
+}
+__device__ inline bool tile_coords(int bid, int Mt, int Nt, int sup_m, int sup_n, int& tm, int& tn, int& sm, int& sn) {
+  const int sNt = (Nt + sup_n - 1) / sup_n, sMt = (Mt + sup_m - 1) / sup_m;
   const int xcd = bid % NXCD, local = bid / NXCD;
-  const int q = local / (SUP_M * SUP_N), within = local % (SUP_M * SUP_N);
+  const int q = local / (sup_m * sup_n), within = local % (sup_m * sup_n);
   const int s = q * NXCD + xcd;
   if (s >= sMt * sNt) return false;
-  sm = within % SUP_M; sn = within / SUP_M;
-  tm = (s / sNt) * SUP_M + sm;
-  tn = (s % sNt) * SUP_N + sn;
+  sm = within % sup_m; sn = within / sup_m;
+  tm = (s / sNt) * sup_m + sm;
+  tn = (s % sNt) * sup_n + sn;
   return tm < Mt && tn < Nt;
 }
 
@@ -134,7 +150,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
   int tm, tn, sm, sn;
-  if (!tile_coords(blockIdx.x, Mt, Nt, tm, tn, sm, sn)) return;
+  if (!tile_coords(blockIdx.x, Mt, Nt, p.sup_m, p.sup_n, tm, tn, sm, sn)) return;
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M || n0 >= N) return;
 
@@ -159,30 +175,36 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const uint16_t* a_ptr[8];
   const uint16_t* b_ptr[8];
   // Workgroups that share a panel (same sm for A, same sn for B) walk its row blocks in a
-  // different cyclic order, so that they do not all ask the L2 for the same lines at the same
-  // moment (1-2 % on the forward and dH launches).
-  const int rot_a = (sn * (8 / SUP_N)) & 7, rot_b = (sm * (8 / SUP_M)) & 7;
+  // different cyclic order (rot_a, rot_b), so that they do not all ask the L2 for the same lines
+  // at the same moment (1-2 % on the forward and dH launches).
   uint32_t lds_a[8], lds_b[8];                        // LDS offset of load i within the wave's 8 KB
+  const float* zt_ptr = nullptr;                      // forward: this lane's entry of the tile's target logits
+  {
+    const int rot_a = (sn * 8 / p.sup_n) & 7, rot_b = (sm * 8 / p.sup_m) & 7;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int ia = (i + rot_a) & 7, ib = (i + rot_b) & 7;
-    lds_a[i] = __builtin_amdgcn_readfirstlane(ia * 1024);
-    lds_b[i] = __builtin_amdgcn_readfirstlane(ib * 1024);
-    const int r = (wave * 8 + ia) * 8 + lrow;         // row within the 256-row panel
-    const int rB = (wave * 8 + ib) * 8 + lrow;
-    const int lchunk = (lane & 7) ^ ((rB >> 1) & 7);
-    const int lchunk_a = A_PERM ? ((lane & 7) ^ (((r >> 1) & 1) | (((r >> 3) & 3) << 1))) : ((lane & 7) ^ ((r >> 1) & 7));
-    int ra = m0 + r; ra = ra < M ? ra : M - 1;
-    int rb = n0 + rB; rb = rb < N ? rb : N - 1;
-    int64_t rowa = ra, rowb = rb;
-    if (MODE == MODE_FWD) rowb = p.row_index[rb];
-    if (A_KMAJOR) {
-      const int k = 2 * (wave * 8 + ia) + (lane >> 5);  // k row within the panel
-      a_ptr[i] = p.A + (int64_t)k * p.lda + m0 + (((lane & 31) ^ (kswz(k) << 1)) << 3);
-    } else {
-      a_ptr[i] = p.A + rowa * p.lda + lchunk_a * 8;
+    for (int i = 0; i < 8; ++i) {
+      const int ia = (i + rot_a) & 7, ib = (i + rot_b) & 7;
+      lds_a[i] = __builtin_amdgcn_readfirstlane(ia * 1024);
+      lds_b[i] = __builtin_amdgcn_readfirstlane(ib * 1024);
+      const int r = (wave * 8 + ia) * 8 + lrow;         // row within the 256-row panel
+      const int rB = (wave * 8 + ib) * 8 + lrow;
+      const int lchunk = (lane & 7) ^ ((rB >> 1) & 7);
+      const int lchunk_a = A_PERM ? ((lane & 7) ^ (((r >> 1) & 1) | (((r >> 3) & 3) << 1))) : ((lane & 7) ^ ((r >> 1) & 7));
+      int ra = m0 + r; ra = ra < M ? ra : M - 1;
+      int rb = n0 + rB; rb = rb < N ? rb : N - 1;
+      int64_t rowa = ra, rowb = rb;
+      if (A_KMAJOR) {
+        const int k = 2 * (wave * 8 + ia) + (lane >> 5);  // k row within the panel
+        a_ptr[i] = p.A + (int64_t)k * p.lda + m0 + (((lane & 31) ^ (kswz(k) << 1)) << 3);
+      } else {
+        a_ptr[i] = p.A + rowa * p.lda + lchunk_a * 8;
+      }
+      b_ptr[i] = p.B + rowb * p.ldb + lchunk * 8;
     }
-    b_ptr[i] = p.B + rowb * p.ldb + lchunk * 8;
+    if (MODE == MODE_FWD) {
+      int n = n0 + wave * 64 + lane; n = n < N ? n : N - 1;
+      zt_ptr = p.zt + n;
+    }
   }
   // The direct load is issued through inline assembly on purpose: the compiler's wait-count
   // pass treats a global load that writes LDS as touching both address spaces and then
@@ -205,6 +227,15 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       load_lds16(a_ptr[i] + kt * a_kstep, st + lds_a[i]);
       load_lds16(b_ptr[i] + koff, st + TILE_BYTES + lds_b[i]);
     }
+  };
+
+  // forward: the tile's 256 target logits travel to LDS with the tile's first panel (4 bytes per
+  // lane, one direct load per wave) and are published by the same barrier, so that the epilogue
+  // starts without a round trip to global memory
+  auto issue_zt = [&]() {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(zt_ptr), "s"(__builtin_amdgcn_readfirstlane(lds_base + PIPE_BYTES + wave * 256))
+                 : "memory");
   };
 
   // ---- fragment read offsets.  A 16x16x32 operand fragment: lane -> row (lane & 15),
@@ -250,13 +281,6 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   };
 
   f32x4 acc[8][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
-
   const int nk = K / BK;
   // Software pipeline.  Panel kt+1 is loaded during the MFMAs of panel kt (double buffer).
   // A panel is 8 groups; group g multiplies the A fragments of 16-row block g (both 32-wide
@@ -330,8 +354,15 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // assignment would make the compiler move accumulators around next to MFMAs it cannot see
   // into.  The last two panels read ahead and load like any other (the panel after the last is
   // a re-fetch of the last one, read into registers nobody uses).
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
   if (nk > 0) {
     issue_loads(0, 0, 0, 8);
+    if (MODE == MODE_FWD) issue_zt();
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
     issue_range(last_k(1), 1, 0, 16);
@@ -372,7 +403,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     for (int j = 0; j < 8; ++j) {
       const int n = ncol_base + j * 16;
       const bool live = n < N;
-      const float c2 = live ? fmaf(p.zt[n], LOG2E, kStashMargin2) : 0.f;
+      const float zt = *reinterpret_cast<const float*>(smem + PIPE_BYTES + (wn * 128 + frow + j * 16) * 4);
+      const float c2 = live ? fmaf(zt, LOG2E, kStashMargin2) : 0.f;
       uint16_t* erow = p.estash + (int64_t)n * p.lde + m0 + wm * 128 + 8 * fq;
       float s = 0.f, t = 0.f;
 #pragma unroll
@@ -488,25 +520,26 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 }
 
 template <int MODE>
-void launch(const Params& p, hipStream_t stream) {
+void launch(Params& p, hipStream_t stream) {
   static LdsLimit lds_limit;
-  lds_limit.ensure(reinterpret_cast<const void*>(&gemm_nt_bf16<MODE>), LDS_BYTES);
+  lds_limit.ensure(reinterpret_cast<const void*>(&gemm_nt_bf16<MODE>), lds_bytes<MODE>());
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
-  const int blocks = num_blocks(Mt, Nt);
-  hipLaunchKernelGGL(gemm_nt_bf16<MODE>, dim3(blocks), dim3(NTHREADS), LDS_BYTES, stream, p);
+  const SuperTile st = pick_super_tile(Nt);
+  p.sup_m = st.m; p.sup_n = st.n;
+  const int blocks = num_blocks(Mt, Nt, st.m, st.n);
+  hipLaunchKernelGGL(gemm_nt_bf16<MODE>, dim3(blocks), dim3(NTHREADS), lds_bytes<MODE>(), stream, p);
 }
 
 }  // namespace
 
-void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index, const float* zt,
+void launch_gemm_fwd_bf16(const void* W, int64_t ldw, const void* Hc, int64_t ldh, int k_len, const float* zt,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
                           int V, int d, float* part_sum, float* part_ez,
                           int64_t part_stride, void* estash, int64_t lde, hipStream_t stream) {
   Params p = {};
-  p.A = static_cast<const uint16_t*>(W); p.lda = d; p.M = V;
-  p.B = static_cast<const uint16_t*>(H); p.ldb = d; p.N = chunk_rows;
-  p.K = d;
-  p.row_index = row_index + chunk_start;
+  p.A = static_cast<const uint16_t*>(W); p.lda = ldw; p.M = V;
+  p.B = static_cast<const uint16_t*>(Hc); p.ldb = ldh; p.N = chunk_rows;
+  p.K = k_len;
   p.n_scored = n_scored; p.chunk_start = chunk_start; p.chunk_rows = chunk_rows;
   p.zt = zt + chunk_start;
   p.part_sum = part_sum; p.part_ez = part_ez; p.part_stride = part_stride;

@@ -51,12 +51,13 @@ constexpr float kSaturatedLogp = -97.f;
 // n_scored: device pointer to the number of compacted rows; chunk_start/chunk_rows
 // select the rows this launch covers (valid rows = clamp(n_scored - chunk_start, 0, chunk_rows)).
 
-// Forward: A = W [V, d], B = H rows gathered through row_index[chunk_start + n]; zt[chunk_start + n]
-// is the row's target logit.  Writes per-row partials part_sum[(2*tile_m + wave_m) * part_stride + n]
+// Forward: A = W [V, k_len] (row stride ldw), B = Hc [chunk_rows, k_len] (row stride ldh): the
+// launch's token rows, gathered and contiguous; k_len = d rounded up to 128, the columns beyond d
+// zero in both operands; zt[chunk_start + n] is the row's target logit.  Writes per-row partials part_sum[(2*tile_m + wave_m) * part_stride + n]
 // = sum of e[n, v] over the partial's 128 vocabulary rows (e as defined above), when part_ez != nullptr
 // also sum e * z (for the entropy), and, when estash != nullptr, e itself as bf16 into
 // estash[n * lde + v] (n = row within this launch; columns V .. round_up(V, 256) get zeros).
-void launch_gemm_fwd_bf16(const void* W, const void* H, const int32_t* row_index, const float* zt,
+void launch_gemm_fwd_bf16(const void* W, int64_t ldw, const void* Hc, int64_t ldh, int k_len, const float* zt,
                           const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
                           int V, int d, float* part_sum, float* part_ez,
                           int64_t part_stride, void* estash, int64_t lde, hipStream_t stream);
@@ -168,6 +169,13 @@ void launch_convert_f32(float* ZP, int64_t ldz, float* Pt, int64_t ldpt, const f
 // contraction runs over pairs of 64-row panels; the forward kernel writes valid rows only).
 void launch_zero_stash_tail(void* estash, int64_t lde, const int64_t* n_scored, int64_t chunk_start,
                             int chunk_rows, int Vp, hipStream_t stream);
+
+// bf16 path: Out[r][0:dp] = In[rows[r]][0:d], zero in [d, dp) (rows == nullptr: identity), for
+// r < valid rows of the chunk (n_scored != nullptr) or r < n_rows_static.  16-byte vectors: d, dp,
+// both row strides multiples of 8 elements.
+void launch_gather_rows_b16(const void* in, int64_t ld_in, const int32_t* rows, void* out, int64_t ld_out,
+                            int64_t n_rows_static, const int64_t* n_scored, int64_t chunk_start,
+                            int chunk_rows, int d, int dp, hipStream_t stream);
 
 // Out[c][r] = scale[r] * In[rows[r]][c] (rows == nullptr: identity; scale == nullptr: 1, 2-byte
 // elements only) for r < n_rows_valid, zero beyond, r in [0, out_cols_pad), c in [0, n_cols).

@@ -56,7 +56,7 @@ def test_token_logprobs_argument_errors():
     assert f(FAKE, FAKE, FAKE, None, -1, 128, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2
     assert f(FAKE, FAKE, FAKE, None, 8, 0, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2
     assert f(FAKE, FAKE, FAKE, None, 8, 64, 0, 1, FAKE, None, FAKE, 1 << 20, None) == -2
-    assert f(FAKE, FAKE, FAKE, None, 8, 72, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2   # bf16: d % 128
+    assert f(FAKE, FAKE, FAKE, None, 8, 36, 32, 1, FAKE, None, FAKE, 1 << 20, None) == -2   # bf16: d % 8
     assert f(FAKE, FAKE, FAKE, None, 0, 128, 32, 1, FAKE, None, None, 0, None) == 0          # N = 0: no-op
     assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, None, 0, None) == -6
     assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, P(0x1001), 1 << 20, None) == -6  # misaligned
@@ -164,7 +164,7 @@ def test_token_scores_argument_errors():
     lib = m.lib()
     f = lib.mrl_token_scores
     assert f(None, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, None, FAKE, 1 << 20, None) == -1
-    assert f(FAKE, FAKE, FAKE, None, 8, 72, 32, 1, FAKE, None, FAKE, FAKE, 1 << 20, None) == -2
+    assert f(FAKE, FAKE, FAKE, None, 8, 36, 32, 1, FAKE, None, FAKE, FAKE, 1 << 20, None) == -2
     assert f(FAKE, FAKE, FAKE, None, 8, 128, 32, 1, FAKE, None, FAKE, FAKE, 16, None) == -6    # workspace too small
     assert f(FAKE, FAKE, FAKE, None, 0, 128, 32, 1, FAKE, None, FAKE, None, 0, None) == 0
     # the entropy needs a third partial buffer: its workspace is the larger one
@@ -177,7 +177,7 @@ def test_static_logprobs_argument_errors():
     f = m.lib().mrl_token_logprobs_static
     one = 8  # any non-null address: rejected arguments are never dereferenced
     assert f(None, one, one, None, 16, 128, 512, 1, one, None, None) == -1
-    assert f(one, one, one, None, 16, 100, 512, 1, one, None, None) == -2        # d % 128
+    assert f(one, one, one, None, 16, 100, 512, 1, one, None, None) == -2        # d % 8
     assert f(one, one, one, None, 16, 128, 512, 7, one, None, None) == -3
     assert f(one, one, one, None, 0, 128, 512, 1, one, None, None) == 0           # empty input: no-op
     assert f(one, one, one, None, 1 << 23, 128, 512, 1, one, None, None) == -10   # 8 B per row > 32 MiB

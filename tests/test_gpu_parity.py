@@ -29,14 +29,23 @@ def _gpu_adv(mrl, batch, mode=1, **kw):
 
 
 def _run_both(mrl, synth, sp, chunk_rows=256, dh_dtype=None, logp_tol=util.LOGP_TOL, rel_tol=util.REL_TOL,
-              adv_mode=1, h_scale=None, loss_agg=0, ratio_level=0, behav_jitter=None):
+              adv_mode=1, h_scale=None, loss_agg=0, ratio_level=0, behav_jitter=None, w_shift=None):
     batch = synth.make(sp, "cuda")
     if h_scale is not None:
         batch["H"] = (batch["H"].float() * h_scale).to(batch["H"].dtype)
+    if h_scale is not None or w_shift is not None:
         centre = synth.logp_proxy(batch["H"], batch["W"], batch["targets"])
         g = torch.Generator("cuda").manual_seed(1)
         batch["behav"] = centre + 0.1 * torch.randn(batch["N"], device="cuda", generator=g)
         batch["ref"] = centre + 0.1 * torch.randn(batch["N"], device="cuda", generator=g)
+    if w_shift is not None:
+        # the same vector added to every row of W moves all logits of a token row by <h, shift>:
+        # the softmax does not change (up to the rounding of W), the magnitude of the logits does;
+        # the traces above stay centred on the unshifted head
+        g = torch.Generator("cuda").manual_seed(3)
+        c = w_shift / (sp.d ** 0.5) * torch.randn(sp.d, device="cuda", generator=g)
+        batch["W"] = (batch["W"].float() + c[None, :]).to(batch["W"].dtype)
+        batch["w_common"] = c.cpu().numpy().astype(np.float64)
     cfg = util.cfg_dict(sp, loss_agg=loss_agg, ratio_level=ratio_level)
     if behav_jitter is not None:
         centre = synth.logp_proxy(batch["H"], batch["W"], batch["targets"])
@@ -85,7 +94,21 @@ def _run_both(mrl, synth, sp, chunk_rows=256, dh_dtype=None, logp_tol=util.LOGP_
 
     dH = util.to_f64(got["dH"])
     assert np.all(dH[~m] == 0.0)
-    util.check_gradient("dH", dH, want["dH"], rel_tol)
+    if w_shift is None:
+        util.check_gradient("dH", dH, want["dH"], rel_tol)
+    else:
+        # dH = dz W.  With a common vector c in every row of W, dH = dz W0 + (sum_v dz) c, and the
+        # exact sum_v dz = 0 is met by bf16 operands only up to their rounding: the component of
+        # dH along c is ill-conditioned for ANY implementation whose dz operand is bf16.  Checked:
+        # the part orthogonal to c to the usual tolerance, the part along c against the bound that
+        # rounding implies, |sum_v delta(dz_v)| |c| <= 2^-9 sum_v |dz_v| |c| <= 2^-8 |g| |c|.
+        c = batch["w_common"]
+        chat = c / np.linalg.norm(c)
+        perp = lambda x: x - np.outer(x @ chat, chat)
+        util.check_gradient("dH orthogonal to the common vector", perp(dH), perp(want["dH"]), rel_tol)
+        along = np.abs((dH - want["dH"]) @ chat)
+        bound = 2.0 ** -8 * np.abs(want["g"]) * np.linalg.norm(c) + 2.0 ** -8 * np.linalg.norm(want["dH"], axis=1)
+        assert np.all(along <= bound + 1e-30), float(np.max(along / np.maximum(bound, 1e-300)))
     util.check_gradient("dW", util.to_f64(got["dW"]), want["dW"], rel_tol)
     return batch, got, want, st
 
@@ -105,6 +128,8 @@ def test_fp32_path_multichunk_ragged(mrl, synth):
     (3, dict(n_prompts=2, T=24, V=3001)),
     (4, dict(n_prompts=5, T=16, V=1000)),
     (5, dict(n_prompts=2, T=48, V=4100, d=512)),
+    (2, dict(n_prompts=2, T=40, V=2500, d=200)),     # width not a multiple of the 128-wide panel pairs: zero-padded operands
+    (3, dict(n_prompts=2, T=24, V=3001, d=328)),     # one and a bit 256-wide tiles of d, ragged everything
 ])
 def test_mini_configs_bf16(mrl, synth, idx, over):
     sp = synth.spec(idx, **over)
@@ -126,6 +151,68 @@ def test_peaked_softmax(mrl, synth):
     # hidden states scaled x8: logits of std ~ 6, exercises the max-subtraction and fp16 stash
     sp = synth.spec(2, n_prompts=2, T=24, V=3000, d=256)
     _run_both(mrl, synth, sp, chunk_rows=256, h_scale=8.0)
+
+
+def test_large_logit_offsets(mrl, synth):
+    """Logits of magnitude 30-100 with an ordinary softmax (a common vector added to every row of
+    W shifts each token row's logits by about N(0, 40)): exponentials are taken relative to the
+    row's target logit, so neither the log-probs nor the backward operands lose accuracy with the
+    size of the logits."""
+    sp = synth.spec(2, n_prompts=2, T=24, V=3000, d=256)
+    batch, got, want, st = _run_both(mrl, synth, sp, chunk_rows=256, w_shift=40.0)
+    z = util.to_f64(batch["H"]) @ util.to_f64(batch["W"]).T
+    assert np.abs(z).max() > 60 and np.median(np.abs(z).max(axis=1)) > 20
+    assert st["n_saturated_rows"] == 0
+
+
+def test_rows_outside_the_representable_range_are_counted_and_dropped(mrl, synth):
+    """A few token rows whose sampled token is (numerically) impossible under the learner: target
+    log-prob far below -97.  They are counted, report a saturated finite log-prob, and drop out of
+    the loss and the gradients; every other row and the totals minus those rows' terms match the
+    oracle."""
+    sp = synth.spec(2, n_prompts=2, T=24, V=3000, d=256)
+    batch = synth.make(sp, "cuda")
+    B, T, G = batch["B"], batch["T"], batch["G"]
+    m = batch["mask"].reshape(-1).bool()
+    scored = torch.nonzero(m)[:, 0]
+    wild = scored[[5, 77, 200]]
+    wild_np = wild.cpu().numpy()
+    batch["H"][wild] = (batch["H"][wild].float() * 120.0).to(torch.bfloat16)     # logits of std ~ 40
+    z = util.to_f64(batch["H"][wild]) @ util.to_f64(batch["W"]).T
+    batch["targets"][wild] = torch.tensor(np.argmin(z, axis=1), dtype=torch.int32, device="cuda")   # the least likely id
+    adv, *_ = util.oracle_advantages(batch)
+    seq_adv = torch.tensor(adv[:B], dtype=torch.float32, device="cuda")
+    cfg = util.cfg_dict(sp)
+    first = util.oracle_loss(batch, adv[:B], cfg, need_grads=False)
+    assert np.all(first["logp"][wild_np] < -150)
+    # keep the oracle's own terms of those rows finite: on-policy and on-reference there
+    batch["behav"] = util.move_off_kinks(batch, first["logp"], sp.clip_eps)
+    batch["behav"][wild] = torch.tensor(first["logp"][wild_np], dtype=torch.float32, device="cuda")
+    batch["ref"][wild] = batch["behav"][wild]
+    want = util.oracle_loss(batch, adv[:B], cfg)
+    lc = mrl.LossConfig(kl_beta=sp.kl_beta, sgt_lambda=sp.sgt_lambda, chunk_rows=256, dh_dtype=mrl.BF16)
+    got = mrl.grpo_loss_fwd_bwd(batch["H"], batch["W"], batch["targets"], batch["mask"].reshape(-1), batch["behav"],
+                                batch["ref"], seq_adv, batch["seq_group"], batch["seq_kind"], B, T, G, lc)
+    torch.cuda.synchronize()
+    st = mrl.read_stats(got["stats"])
+    assert st["n_saturated_rows"] == 3 and st["n_scored_tokens"] == int(m.sum())
+    assert torch.isfinite(got["logp"]).all() and torch.isfinite(got["dH"].float()).all() and torch.isfinite(got["dW"]).all()
+    assert torch.all(got["logp"][wild] < -97) and torch.all(got["dH"][wild] == 0)
+    ok = m.clone()
+    ok[wild] = False
+    okn = ok.cpu().numpy()
+    assert np.max(np.abs(got["logp"].cpu().numpy()[okn] - want["logp"][okn])) <= util.LOGP_TOL
+    dH_want = want["dH"].copy()
+    dH_want[wild_np] = 0.0
+    util.check_gradient("dH", util.to_f64(got["dH"]), dH_want)
+    _, dW_wild, _ = orc.head_backward(util.to_f64(batch["H"][wild]), util.to_f64(batch["W"]),
+                                      batch["targets"][wild].cpu().numpy(), want["g"][wild_np])
+    util.check_gradient("dW", util.to_f64(got["dW"]), want["dW"] - dW_wild)
+    # loss: the oracle's total minus the dropped rows' terms (J = A at ratio 1, k3 = 0 there)
+    J = np.minimum(want["s1"], want["s2"])
+    pg = want["loss_pg"] + float(np.sum(want["c"][wild_np] * J[wild_np]))
+    assert abs(st["loss_pg"] - pg) <= 1e-4 * float(np.sum(want["c"] * np.abs(J)))
+    assert abs(st["loss_kl"] - want["loss_kl"]) <= 1e-2 * want["loss_kl"]
 
 
 def test_global_token_mean_and_batch_zn(mrl, synth):
