@@ -224,19 +224,22 @@ def main():
                for k, v in prof.items()}
     # HBM-bound passes: algorithmic bytes per step / measured time of the class
     Vp = (V + 255) // 256 * 256
+    dp = (d + 127) // 128 * 128
     n_part = 2 * (Vp // 256)
     alg_bytes = dict(
         # mask + target scans (count, fill, sequence lengths), row index, zero fill of the unscored
         # slots' dH rows and log-probs, target logits (one H row and one W row per scored token)
         prep=3 * N * 5 + 4 * n_scored + (N - n_scored) * (2 * d + 4) + n_scored * (4 * d + 12),
         adv=B * 22 + G * 9,
-        # (max, sum-exp) partials and the per-token inputs / outputs of Eq. (1)
-        row_epilogue=n_scored * (8 * n_part + 32),
-        # fp16 logits in, bf16 dz out, plus the transposed copy of the pass's hidden rows
-        convert=n_scored * (4 * Vp + 4 * d))
+        # partial sums of the forward launches, the per-token inputs / outputs of Eq. (1), the row
+        # scale and the patched target column of the stash
+        row_epilogue=n_scored * (4 * n_part + 36),
+        # gathered copy of each pass's hidden rows, their scaled transpose for the dW launch, and
+        # (once per step) the transpose of W for the dH launch
+        operand_prep=n_scored * (2 * d + 2 * dp) + n_scored * 4 * dp + V * d * 2 + Vp * dp * 2)
     hbm_passes = {k: dict(algorithmic_GB=round(b / 1e9, 3),
                           achieved_GBps=round(b * args.steps / (prof[k][0] * 1e-3) / 1e9, 1) if prof[k][0] > 0 else None,
-                          peak_GBps=8000.0)
+                          peak_GBps=8000.0, source="HIP events over the class's launches; counters in profiles/")
                   for k, b in alg_bytes.items()}
 
     # what the matrix cores sustain on this machine with no memory traffic: clock-limited (constant

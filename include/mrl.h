@@ -282,7 +282,7 @@ enum {
   MRL_PROF_ADV = 1,       /* group advantages */
   MRL_PROF_GEMM_FWD = 2,  /* logits tile GEMM with fused log-sum-exp */
   MRL_PROF_ROW_EPI = 3,   /* partial merge, ratio / clip / KL, loss partials */
-  MRL_PROF_CONVERT = 4,   /* logits -> dz conversion and operand transposes */
+  MRL_PROF_CONVERT = 4,   /* operand preparation: row gather, transposes (fp32 path: logits -> dz) */
   MRL_PROF_GEMM_DH = 5,   /* dH = dz W */
   MRL_PROF_GEMM_DW = 6,   /* dW += dz^T H */
   MRL_PROF_FINAL = 7,     /* final reductions */

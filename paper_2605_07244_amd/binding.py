@@ -16,7 +16,7 @@ import torch
 
 F32, BF16 = 0, 1
 ADV_CENTER, ADV_GROUP_ZN, ADV_BATCH_ZN = 0, 1, 2
-PROF_CLASSES = ("prep", "adv", "gemm_fwd", "row_epilogue", "convert", "gemm_dh", "gemm_dw", "final")
+PROF_CLASSES = ("prep", "adv", "gemm_fwd", "row_epilogue", "operand_prep", "gemm_dh", "gemm_dw", "final")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
