@@ -271,27 +271,6 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden /*[B*T,d] dev*/, const void* lm_hea
                           void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Per-kernel-class timing for benchmarks.  When enabled, every kernel launch
- * of the calls above is bracketed by HIP events on the launch stream.
- * mrl_profile_collect synchronises the device, adds up the elapsed time and
- * launch count per class since the last collect, and resets the log.
- * Arrays are HOST memory of MRL_PROF_NCLASS entries.
- * ---------------------------------------------------------------------- */
-enum {
-  MRL_PROF_PREP = 0,      /* mask scan, compaction, sequence weights, zero fill */
-  MRL_PROF_ADV = 1,       /* group advantages */
-  MRL_PROF_GEMM_FWD = 2,  /* logits tile GEMM with fused log-sum-exp */
-  MRL_PROF_ROW_EPI = 3,   /* partial merge, ratio / clip / KL, loss partials */
-  MRL_PROF_CONVERT = 4,   /* operand preparation: row gather, transposes (fp32 path: logits -> dz) */
-  MRL_PROF_GEMM_DH = 5,   /* dH = dz W */
-  MRL_PROF_GEMM_DW = 6,   /* dW += dz^T H */
-  MRL_PROF_FINAL = 7,     /* final reductions */
-  MRL_PROF_NCLASS = 8
-};
-int mrl_profile_enable(int on);
-int mrl_profile_collect(double* ms_per_class /*host*/, int64_t* launches_per_class /*host*/);
-
-/* ------------------------------------------------------------------------
  * (4) THL word-level trace alignment on integer word maps (Sec. 4.3; App. D,
  *     "THL WordAlignLogProbs", Alg. 2).  A peer's per-token log-probs on its own
  *     token grid (source) are carried over to the learner's grid (target): the
@@ -328,22 +307,6 @@ int mrl_thl_word_align(const float* src_logp /*[B,S_src] dev*/, const uint8_t* s
                        const int32_t* tgt_map_len /*[B] dev*/, int64_t B, int32_t S_src, int32_t S_tgt,
                        int32_t max_words, float ignore_value, float* out /*[B,S_tgt] dev*/,
                        int64_t* out_bad_words /*[1] dev | NULL*/, void* stream);
-
-/* ------------------------------------------------------------------------
- * Diagnostic: sustained rate of the matrix cores on the MFMA instruction the
- * GEMM kernels use (bf16 16x16x32, fp32 accumulate), registers only, no memory
- * traffic.  random_operands = 0: constant operands (clock-limited peak);
- * 1: random sign / mantissa operands, which is what activations and weights
- * look like - the device lowers its clock under the higher switching power, so
- * this is the ceiling of any bf16 GEMM on real data.  Benchmarks print both
- * next to the published peak (Sec. 3 defines the contraction this bounds).
- * Synchronous: runs on the null stream for about `seconds` (0 < seconds <= 5)
- * and waits.  scratch: device memory, at least 1024 bytes per compute unit
- * (512 KiB is enough for any device); out_tflops: host.  Errors: MRL_ERR_NULL,
- * MRL_ERR_CONFIG (seconds), MRL_ERR_WORKSPACE (scratch too small), MRL_ERR_DEVICE.
- * ---------------------------------------------------------------------- */
-int mrl_probe_mfma_rate(int32_t random_operands, double seconds, void* scratch /*dev*/,
-                        size_t scratch_bytes, double* out_tflops /*host*/);
 
 #ifdef __cplusplus
 }

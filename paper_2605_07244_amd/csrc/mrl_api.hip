@@ -1,6 +1,7 @@
 // C ABI of the scoring library: argument validation, workspace carving and the
 // launch sequence of the hot path.  See include/mrl.h for the contract.
 #include "../../include/mrl.h"
+#include "../../include/mrl_diag.h"
 #include "mrl_internal.h"
 
 #include <cstring>

@@ -7,6 +7,7 @@
 // bf16 GEMM can reach on such data.  Benchmarks report both beside the
 // published peak.
 #include "../../include/mrl.h"
+#include "../../include/mrl_diag.h"
 #include "mrl_internal.h"
 
 namespace mrl {
