@@ -310,42 +310,52 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st + lds_a[j >> 1]);
     }
   };
-  auto panel = [&](int set, int st_cur, int st_nxt, int kt_load, int slot_load) {
-#pragma unroll
-    for (int g = 0; g < 8; ++g) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        mfma16(acc[g][j], fax[g & 3][0], fbx[set][0][j]);
-        mfma16(acc[g][j], fax[g & 3][1], fbx[set][1][j]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      if (g == 4) {
-        // this thread's part of panel kt+1 has landed, then everyone's; every wave has issued its
-        // last read of panel kt's slot a group ago, so the slot can be refilled
+  // One panel = 8 groups of 16 MFMAs.  A wave issues in order and the matrix pipe takes a new MFMA
+  // only every 16 cycles, so whatever stands between two MFMAs in the instruction stream is free
+  // as long as it fits the 12 issue cycles the pipe leaves over - and costs pipe time when it
+  // comes as a block after the sixteenth.  The side work of a panel (fragment reads, the barrier,
+  // direct loads with their address arithmetic) is therefore cut into pieces of one to four
+  // instructions, one piece after an MFMA, in source order (both are volatile assembly or fenced):
+  //   group 0      : A fragments of row block 3 (this panel); last 4 loads of the NEXT panel's slot
+  //   groups 1 - 4 : A fragments of row blocks 4 - 7
+  //   group 5      : wait for this thread's part of panel kt+1, barrier (every wave has issued its
+  //                  last read of this panel's slot by then, so the slot can be refilled; panel
+  //                  kt+1 becomes visible); next panel's A block 0, B column blocks 0 - 2; loads 0 - 3
+  //                  of panel kt+2 into this panel's slot
+  //   group 6      : next A block 1, B blocks 3 - 5, loads 4 - 7
+  //   group 7      : next A block 2, B blocks 6 - 7, loads 8 - 11   (loads 12 - 15 follow in group 0
+  //                  of the next panel)
+  // A fragments sit in a ring of four pairs: group g multiplies ring slot g % 4, and the slot a
+  // group has just finished with is refilled during the next group.
+  auto side = [&](int g, int m, int set, int st_cur, int st_nxt, int kt_nxt, int slot_nxt, int kt_load, int slot_cur) {
+    if (g == 0) {
+      if (m < 2) fax[3][m] = read_a(st_cur, m, 3);
+      if (m >= 4 && m < 16 && (m - 4) % 3 == 0) { const int l = 12 + (m - 4) / 3; issue_range(kt_nxt, slot_nxt, l, l + 1); }
+    } else if (g <= 4) {
+      if (m < 2) fax[(g - 1) & 3][m] = read_a(st_cur, m, g + 3);
+    } else {
+      const int q = g - 5;                          // 0, 1, 2
+      if (g == 5 && m == 0) {
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
         __syncthreads();
       }
-      if (g < 4) {
-        fax[g & 3][0] = read_a(st_cur, 0, g + 4);
-        fax[g & 3][1] = read_a(st_cur, 1, g + 4);
-      } else {
-        fax[g & 3][0] = read_a(st_nxt, 0, g - 4);
-        fax[g & 3][1] = read_a(st_nxt, 1, g - 4);
-      }
-      if (g >= 4) {
-        // next B set in groups 4-6: column blocks 0-2, 3-5, 6-7, so that the last of them are
-        // issued a whole group before the next panel starts; direct loads of the panel after
-        // next, four per group
-        if (g < 7) {
+      if (m >= 1 && m < 3) fax[q][m - 1] = read_a(st_nxt, m - 1, q);
+      const int nb = q == 2 ? 2 : 3;                // B column blocks read in this group
+      if (m >= 3 && m < 3 + 2 * nb) { const int j = 3 * q + (m - 3) / 2, ks = (m - 3) & 1; fbx[set ^ 1][ks][j] = read_b(st_nxt, ks, j); }
+      // four loads in the remaining gaps
+      const int first = 3 + 2 * nb;                 // 9, 9, 7
+      if (m >= first && (m - first) % 2 == 0 && (m - first) / 2 < 4) { const int l = 4 * q + (m - first) / 2; issue_range(kt_load, slot_cur, l, l + 1); }
+    }
+  };
+  auto panel = [&](int set, int st_cur, int st_nxt, int kt_nxt, int slot_nxt, int kt_load, int slot_cur) {
 #pragma unroll
-          for (int j = (g - 4) * 3; j < (g == 6 ? 8 : (g - 3) * 3); ++j) {
-            fbx[set ^ 1][0][j] = read_b(st_nxt, 0, j);
-            fbx[set ^ 1][1][j] = read_b(st_nxt, 1, j);
-          }
-        }
-        issue_range(kt_load, slot_load, (g - 4) * 4, (g - 3) * 4);
+    for (int g = 0; g < 8; ++g) {
+#pragma unroll
+      for (int m = 0; m < 16; ++m) {
+        mfma16(acc[g][m >> 1], fax[g & 3][m & 1], fbx[set][m & 1][m >> 1]);
+        side(g, m, set, st_cur, st_nxt, kt_nxt, slot_nxt, kt_load, slot_cur);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
   };
   auto last_k = [&](int k) { return k < nk ? k : nk - 1; };
@@ -365,14 +375,14 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     if (MODE == MODE_FWD) issue_zt();
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
-    issue_range(last_k(1), 1, 0, 16);
+    issue_range(last_k(1), 1, 0, 12);            // its last four loads come with group 0 of the first panel
 #pragma unroll
     for (int j = 0; j < 8; ++j) { fbx[0][0][j] = read_b(0, 0, j); fbx[0][1][j] = read_b(0, 1, j); }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { fax[i][0] = read_a(0, 0, i); fax[i][1] = read_a(0, 1, i); }
+    for (int i = 0; i < 3; ++i) { fax[i][0] = read_a(0, 0, i); fax[i][1] = read_a(0, 1, i); }
     for (int kt = 0; kt < nk; kt += 2) {
-      panel(0, 0, STAGE_BYTES, last_k(kt + 2), 0);
-      panel(1, STAGE_BYTES, 0, last_k(kt + 3), 1);
+      panel(0, 0, STAGE_BYTES, last_k(kt + 1), 1, last_k(kt + 2), 0);
+      panel(1, STAGE_BYTES, 0, last_k(kt + 2), 0, last_k(kt + 3), 1);
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));   // no direct load may outlive the wave
     drain_mfma(acc[7]);
