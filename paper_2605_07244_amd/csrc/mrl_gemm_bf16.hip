@@ -46,6 +46,17 @@ constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + B
 constexpr int DHSTAGE_LD = BM + 8;                   // bf16 elements per row of the dH epilogue's staging tile
 constexpr int DHSTAGE_BYTES = BN * DHSTAGE_LD * 2;     // 132 KB
 constexpr int PIPE_BYTES = NSTAGE * STAGE_BYTES;   // 128 KB
+// Direct loads of a slot's 16 (per wave), by the group of the K loop that issues them: the slot is
+// released by the barrier in group 5, so its refill starts there and may run on into groups 0 - 4
+// of the next panel (it is needed at that panel's barrier).
+constexpr int kLoadsInGroup[8] = {4, 0, 0, 0, 0, 4, 4, 4};
+constexpr int load_index_base(int g) {      // loads issued before group g, in the order 5, 6, 7, 0, 1, ...
+  int n = 0;
+  for (int h = 5; h != g; h = (h + 1) & 7) n += kLoadsInGroup[h];
+  return n;
+}
+constexpr int kLoadsCarriedOver = kLoadsInGroup[0] + kLoadsInGroup[1] + kLoadsInGroup[2] + kLoadsInGroup[3] + kLoadsInGroup[4];
+static_assert(kLoadsCarriedOver + kLoadsInGroup[5] + kLoadsInGroup[6] + kLoadsInGroup[7] == 16, "a slot takes 16 loads per wave");
 constexpr int ZT_BYTES = BN * 4;                   // forward: the tile's 256 target logits, behind the panels
 template <int MODE> constexpr int lds_bytes() {
   return MODE == 0 ? PIPE_BYTES + ZT_BYTES : (DHSTAGE_BYTES > PIPE_BYTES ? DHSTAGE_BYTES : PIPE_BYTES);
@@ -289,12 +300,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // touching 64 different ones in turn (about 5 % more FLOP/s from an MFMA-only loop at the
   // power limit), which is what bounds these kernels on real data.
   // Registers: the B fragments of a whole panel stay resident, in two sets (this panel / the
-  // next one); A fragments sit in a ring of four pairs and are read four groups ahead, at the end
-  // of the group that used the ring slot.  So the last read of panel kt's LDS slot is issued in
-  // group 3; the barrier after group 4 releases that slot and publishes panel kt+1 (whose loads
-  // were issued in groups 4-7 of panel kt-1); groups 4-6 then read the next B set and groups 4-7
-  // issue the direct loads of panel kt+2 into the released slot, each in the shadow of a group's
-  // MFMAs.
+  // next one); A fragments sit in a ring of four pairs.  The schedule of reads, barrier and
+  // direct loads around the MFMAs is described at `side` below.
   // The loop body (two panels, so that the B sets have fixed registers) is branch-free; loads
   // that would run past the end re-fetch the last panel into a slot nobody reads.
   bf16x8 fbx[2][2][8];   // [set][K step][16-column block]
@@ -302,12 +309,20 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   auto read_b = [&](int st, int ks, int j) -> bf16x8 {
     return *reinterpret_cast<const bf16x8*>(smem + st + b_off[ks] + j * 2048);
   };
+  // One load of the K loop: three instructions, what one MFMA leaves room for.  The address
+  // arithmetic (panel offset, uniform) is part of the piece, and it separates the write of M0
+  // from the load that reads it (one wait state).
+  auto load_lds16_at = [](const uint16_t* base, int64_t byte_off, uint32_t lds_addr) {
+    uint64_t addr;
+    asm volatile("s_mov_b32 m0, %3\n\tv_lshl_add_u64 %0, %1, 0, %2\n\tglobal_load_lds_dwordx4 %0, off"
+                 : "=&v"(addr) : "v"(base), "s"(byte_off), "s"(lds_addr) : "memory");
+  };
   auto issue_range = [&](int kt, int slot, int j0, int j1) {
 #pragma unroll
     for (int j = j0; j < j1; ++j) {
       const uint32_t st = slot * STAGE_BYTES + wave_lds;
-      if (j & 1) load_lds16(b_ptr[j >> 1] + kt * BK, st + TILE_BYTES + lds_b[j >> 1]);
-      else load_lds16(a_ptr[j >> 1] + kt * a_kstep, st + lds_a[j >> 1]);
+      if (j & 1) load_lds16_at(b_ptr[j >> 1], (int64_t)kt * (BK * 2), st + TILE_BYTES + lds_b[j >> 1]);
+      else load_lds16_at(a_ptr[j >> 1], (int64_t)kt * a_kstep * 2, st + lds_a[j >> 1]);
     }
   };
   // One panel = 8 groups of 16 MFMAs.  A wave issues in order and the matrix pipe takes a new MFMA
@@ -316,21 +331,26 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // comes as a block after the sixteenth.  The side work of a panel (fragment reads, the barrier,
   // direct loads with their address arithmetic) is therefore cut into pieces of one to four
   // instructions, one piece after an MFMA, in source order (both are volatile assembly or fenced):
-  //   group 0      : A fragments of row block 3 (this panel); last 4 loads of the NEXT panel's slot
+  //   group 0      : A fragments of row block 3 (this panel); the last loads of the NEXT panel's slot
   //   groups 1 - 4 : A fragments of row blocks 4 - 7
   //   group 5      : wait for this thread's part of panel kt+1, barrier (every wave has issued its
   //                  last read of this panel's slot by then, so the slot can be refilled; panel
-  //                  kt+1 becomes visible); next panel's A block 0, B column blocks 0 - 2; loads 0 - 3
-  //                  of panel kt+2 into this panel's slot
-  //   group 6      : next A block 1, B blocks 3 - 5, loads 4 - 7
-  //   group 7      : next A block 2, B blocks 6 - 7, loads 8 - 11   (loads 12 - 15 follow in group 0
-  //                  of the next panel)
+  //                  kt+1 becomes visible); next panel's A block 0, B column blocks 0 - 2; the first
+  //                  loads of panel kt+2 into this panel's slot
+  //   group 6      : next A block 1, B blocks 3 - 5, loads
+  //   group 7      : next A block 2, B blocks 6 - 7, loads   (the rest follows in group 0 of the
+  //                  next panel; kLoadsInGroup says how many where)
   // A fragments sit in a ring of four pairs: group g multiplies ring slot g % 4, and the slot a
-  // group has just finished with is refilled during the next group.
+  // group has just finished with is refilled during the next group.  Four loads per group over
+  // four groups measured best: packing them into groups 5 - 7 costs 2 - 4 % (the load path of a
+  // compute unit takes about 23 cycles per 1 KB load, four waves issuing one every 16 cycles run
+  // its queue full and stall their MFMAs with it), spreading them further leaves the late ones
+  // too little time to land.
   auto side = [&](int g, int m, int set, int st_cur, int st_nxt, int kt_nxt, int slot_nxt, int kt_load, int slot_cur) {
+    // pieces before the loads: the barrier (group 5) and the fragment reads
+    int nr = 2;
     if (g == 0) {
       if (m < 2) fax[3][m] = read_a(st_cur, m, 3);
-      if (m >= 4 && m < 16 && (m - 4) % 3 == 0) { const int l = 12 + (m - 4) / 3; issue_range(kt_nxt, slot_nxt, l, l + 1); }
     } else if (g <= 4) {
       if (m < 2) fax[(g - 1) & 3][m] = read_a(st_cur, m, g + 3);
     } else {
@@ -342,9 +362,19 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       if (m >= 1 && m < 3) fax[q][m - 1] = read_a(st_nxt, m - 1, q);
       const int nb = q == 2 ? 2 : 3;                // B column blocks read in this group
       if (m >= 3 && m < 3 + 2 * nb) { const int j = 3 * q + (m - 3) / 2, ks = (m - 3) & 1; fbx[set ^ 1][ks][j] = read_b(st_nxt, ks, j); }
-      // four loads in the remaining gaps
-      const int first = 3 + 2 * nb;                 // 9, 9, 7
-      if (m >= first && (m - first) % 2 == 0 && (m - first) / 2 < 4) { const int l = 4 * q + (m - first) / 2; issue_range(kt_load, slot_cur, l, l + 1); }
+      nr = 3 + 2 * nb;
+    }
+    // this group's share of the 16 loads that fill a slot, spread over the remaining gaps
+    const int nl = kLoadsInGroup[g];
+    if (nl > 0 && m >= nr) {
+      const int room = 16 - nr;
+#pragma unroll
+      for (int i = 0; i < nl; ++i)
+        if (m == nr + i * room / nl) {
+          const int l = load_index_base(g) + i;
+          if (g >= 5) issue_range(kt_load, slot_cur, l, l + 1);
+          else issue_range(kt_nxt, slot_nxt, l, l + 1);
+        }
     }
   };
   auto panel = [&](int set, int st_cur, int st_nxt, int kt_nxt, int slot_nxt, int kt_load, int slot_cur) {
@@ -375,7 +405,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     if (MODE == MODE_FWD) issue_zt();
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
-    issue_range(last_k(1), 1, 0, 12);            // its last four loads come with group 0 of the first panel
+    issue_range(last_k(1), 1, 0, 16 - kLoadsCarriedOver);   // the rest comes with the first groups of the first panel
 #pragma unroll
     for (int j = 0; j < 8; ++j) { fbx[0][0][j] = read_b(0, 0, j); fbx[0][1][j] = read_b(0, 1, j); }
 #pragma unroll
