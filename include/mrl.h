@@ -104,10 +104,11 @@ int mrl_token_logprobs(const void* hidden /*[N,d] dev*/, const void* lm_head_w /
  *      The scratch space is a buffer of MRL_STATIC_SCRATCH_BYTES built into the library's device
  *      image: every GPU the library runs on holds one copy from the first call until the process
  *      ends.  The call allocates and frees nothing, on the host side of HIP or the device.
- *      Limits: the buffer must hold about 8 bytes per row of N plus 16 bytes per vocabulary id
- *      (the partial sums of the smallest pass, 256 rows); at V = 151936 that allows N up to about
- *      3.8 million rows.  An input beyond the limit returns MRL_ERR_SCRATCH_LIMIT and launches
- *      nothing.
+ *      Limits: the buffer must hold about 8 bytes per row of N plus, for the smallest pass of
+ *      256 rows, 8 bytes per vocabulary id (partial sums) and 512 bytes per hidden column (the
+ *      pass's gathered rows); at V = 151936, d = 4096 that allows N up to about 3.7 million rows.
+ *      Widths that are not a multiple of 128 also need a padded copy of lm_head_w in the buffer.
+ *      An input beyond the limit returns MRL_ERR_SCRATCH_LIMIT and launches nothing.
  *      All calls on one GPU share that GPU's buffer: two calls whose work overlaps in time on the
  *      same GPU (different streams, or different host threads) race on it and give undefined
  *      results; calls on one stream, or otherwise ordered, are fine.  Nothing in the buffer needs
