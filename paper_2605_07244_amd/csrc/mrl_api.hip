@@ -104,6 +104,7 @@ struct Layout {
   size_t total = 0;
   size_t counters, row_index, block_counts, zt, part_max, part_sum, part_ez;
   size_t seq_len, seq_coef, seq_expo, group_count, lse_c, g_c, row_scale, loss_partials, Z, Pt, Ht, Wt;
+  size_t dw_tail = 0;          // bf16: partial tiles of the dW launch's K-split tail
   size_t Hc = 0, Wp = 0;       // bf16: the pass's token rows, gathered and zero-padded to dp columns; W padded likewise (only if dp != d)
   int dp = 0;                  // bf16: d rounded up to the 128-wide panel pairs of the GEMM kernels
   int64_t ldh = 0;             // row stride of Hc and Wp
@@ -161,6 +162,7 @@ Layout make_layout(int64_t N, int64_t B, int d, int V, int dtype, int chunk_rows
     L.Pt = bf16 ? 0 : take(off, (size_t)L.Vp * L.ldr * es);   // fp32 path only: the bf16 dW GEMM reads P itself
     L.Ht = take(off, (size_t)dk * L.ldr * es);
     L.Wt = take(off, (size_t)dk * L.ldz * es);
+    if (bf16) L.dw_tail = take(off, gemm_dw_tail_bytes());
   } else if (!bf16) {
     L.Z = take(off, (size_t)chunk_rows * L.ldz * es);
   }
@@ -581,7 +583,7 @@ int mrl_grpo_loss_fwd_bwd(const void* hidden, const void* lm_head_w, const int32
       const int overwrite = (c == 0 && !cfg->accumulate_dw) ? 1 : 0;
       if (bf16) {
         launch_gemm_dw_bf16(at<void>(ws, L.Z), L.ldz, at<void>(ws, L.Ht), L.ldr, n_scored, c0,
-                            L.chunk_rows, V, d, out_dW, overwrite, s);
+                            L.chunk_rows, V, d, out_dW, overwrite, at<float>(ws, L.dw_tail), s);
       } else {
         GemmF32Args g = {};
         g.A = at<float>(ws, L.Pt); g.lda = L.ldr; g.a_rows = nullptr;

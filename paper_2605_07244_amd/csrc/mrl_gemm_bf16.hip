@@ -57,6 +57,7 @@ constexpr int load_index_base(int g) {      // loads issued before group g, in t
 }
 constexpr int kLoadsCarriedOver = kLoadsInGroup[0] + kLoadsInGroup[1] + kLoadsInGroup[2] + kLoadsInGroup[3] + kLoadsInGroup[4];
 static_assert(kLoadsCarriedOver + kLoadsInGroup[5] + kLoadsInGroup[6] + kLoadsInGroup[7] == 16, "a slot takes 16 loads per wave");
+constexpr int kDwTailMaxItems = 256;                // K slices of dW tail tiles per launch: one per compute unit
 constexpr int ZT_BYTES = BN * 4;                   // forward: the tile's 256 target logits, behind the panels
 template <int MODE> constexpr int lds_bytes() {
   return MODE == 0 ? PIPE_BYTES + ZT_BYTES : (DHSTAGE_BYTES > PIPE_BYTES ? DHSTAGE_BYTES : PIPE_BYTES);
@@ -81,6 +82,10 @@ struct Params {
   const float* row_scale; void* dH; int dh_f32; int d;
   // DW
   float* dW; int overwrite;
+  // DW, K-split tail (see dw_tail_plan): workgroups from main_blocks on take the tiles of the
+  // tile rows tail_m0 .. tail_m0 + tail_rows - 1, each cut into tail_split slices of the
+  // contraction, and store their accumulators to tail_part instead of dW
+  int main_blocks, tail_m0, tail_rows, tail_split; float* tail_part;
 };
 
 // Workgroup -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs, each with its own
@@ -161,7 +166,31 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
   int tm, tn, sm, sn;
-  if (!tile_coords(blockIdx.x, Mt, Nt, p.sup_m, p.sup_n, tm, tn, sm, sn)) return;
+  int k_first = 0;                 // first K panel of this workgroup (DW tail slices start later)
+  float* tail_out = nullptr;       // DW tail slice: where the accumulators go instead of dW
+  if (MODE == MODE_DW && p.tail_split > 0) {
+    if ((int)blockIdx.x < p.main_blocks) {
+      if (!tile_coords(blockIdx.x, p.tail_m0, Nt, p.sup_m, p.sup_n, tm, tn, sm, sn)) return;
+    } else {
+      // one XCD takes consecutive items, i.e. (when the counts divide) all tiles of one slice:
+      // they walk the same K range and share its operand panels in that L2
+      const int e = blockIdx.x - p.main_blocks;
+      const int tiles = p.tail_rows * Nt, items = tiles * p.tail_split;
+      const int per_xcd = (items + NXCD - 1) / NXCD;
+      const int item = (e % NXCD) * per_xcd + e / NXCD;
+      if (e / NXCD >= per_xcd || item >= items) return;
+      const int slice = item / tiles, t = item % tiles;
+      sm = t / Nt; sn = t % Nt;
+      tm = p.tail_m0 + sm; tn = sn;
+      // slices of an even number of panels (the loop body is two panels)
+      const int nk_all = K / BK;
+      const int per = ((nk_all + p.tail_split - 1) / p.tail_split + 1) & ~1;
+      k_first = slice * per;
+      const int k_end = k_first + per < nk_all ? k_first + per : nk_all;
+      K = k_end > k_first ? (k_end - k_first) * BK : 0;
+      tail_out = p.tail_part + (int64_t)item * (BM * BN);
+    }
+  } else if (!tile_coords(blockIdx.x, Mt, Nt, p.sup_m, p.sup_n, tm, tn, sm, sn)) return;
   const int m0 = tm * BM, n0 = tn * BN;
   if (m0 >= M || n0 >= N) return;
 
@@ -206,11 +235,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
       int64_t rowa = ra, rowb = rb;
       if (A_KMAJOR) {
         const int k = 2 * (wave * 8 + ia) + (lane >> 5);  // k row within the panel
-        a_ptr[i] = p.A + (int64_t)k * p.lda + m0 + (((lane & 31) ^ (kswz(k) << 1)) << 3);
+        a_ptr[i] = p.A + ((int64_t)k_first * BK + k) * p.lda + m0 + (((lane & 31) ^ (kswz(k) << 1)) << 3);
       } else {
         a_ptr[i] = p.A + rowa * p.lda + lchunk_a * 8;
       }
-      b_ptr[i] = p.B + rowb * p.ldb + lchunk * 8;
+      b_ptr[i] = p.B + rowb * p.ldb + lchunk * 8 + (MODE == MODE_DW ? k_first * BK : 0);
     }
     if (MODE == MODE_FWD) {
       int n = n0 + wave * 64 + lane; n = n < N ? n : N - 1;
@@ -528,35 +557,78 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   } else {
     // rows = vocabulary ids, cols = hidden index; fp32 accumulate into dW.  The old values of
     // one 16-row band are fetched as a batch before any store, so their latencies overlap.
+    // A K slice of a tail tile stores its partial tile as it is, [256][256] fp32, to the scratch
+    // area instead (dw_tail_reduce adds the slices in their order): the same code with the
+    // tile's own origin, row stride and bounds.
+    const bool tail = tail_out != nullptr;
+    float* const dst = tail ? tail_out : p.dW;
+    const int64_t ld = tail ? BN : p.d;
+    const int v_org = tail ? m0 : 0, n_org = tail ? n0 : 0;
+    const int v_end = tail ? m0 + BM : p.V, n_end = tail ? n0 + BN : p.d;
+    const bool overwrite = tail || p.overwrite;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float old[8][4];
-      if (!p.overwrite) {
+      if (!overwrite) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int v = mrow_base + i * 16 + e;
-          const float* row = p.dW + (int64_t)(v < p.V ? v : p.V - 1) * p.d;
+          const float* row = dst + (int64_t)((v < v_end ? v : v_end - 1) - v_org) * ld - n_org;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const int n = ncol_base + j * 16;
-            old[j][e] = row[n < p.d ? n : p.d - 1];
+            old[j][e] = row[n < n_end ? n : n_end - 1];
           }
         }
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int v = mrow_base + i * 16 + e;
-        if (v < p.V) {
-          float* row = p.dW + (int64_t)v * p.d;
+        if (v < v_end) {
+          float* row = dst + (int64_t)(v - v_org) * ld - n_org;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const int n = ncol_base + j * 16;
-            if (n < p.d) row[n] = p.overwrite ? acc[i][j][e] : old[j][e] + acc[i][j][e];
+            if (n < n_end) row[n] = overwrite ? acc[i][j][e] : old[j][e] + acc[i][j][e];
           }
         }
       }
     }
   }
+}
+
+// dW tail.  The workgroup -> tile mapping runs whole super-tile rows of sup_m tile rows; V / 256
+// tile rows leave a last, ragged super-tile row (2 tile rows x 16 tiles at V = 151936, d = 4096)
+// that keeps an eighth of the compute units busy for the time of a full tile while the others
+// idle: 2.3 % of the launch.  Those tiles are cut into up to 8 slices of the contraction (the
+// pass's token rows) so that the tail is as many work items as there are compute units, each an
+// eighth as long.  The slices store their accumulators to a scratch area and dw_tail_reduce
+// adds them, slice 0 first, into dW: the result does not depend on execution order.
+struct DwTailPlan { int m0, rows, split; };
+inline DwTailPlan dw_tail_plan(int Mt, int Nt, int sup_m) {
+  DwTailPlan t = {Mt / sup_m * sup_m, Mt % sup_m, 0};
+  const int tiles = t.rows * Nt;
+  if (tiles > 0 && t.m0 > 0) {
+    const int s = kDwTailMaxItems / tiles;
+    t.split = s >= 8 ? 8 : (s >= 2 ? s : 0);
+  }
+  return t;
+}
+
+__global__ __launch_bounds__(256) void dw_tail_reduce(const float* __restrict__ part, int tiles, int split, int Nt,
+                                                      int tail_m0, int V, int d, float* __restrict__ dW,
+                                                      int overwrite, const int64_t* __restrict__ n_scored,
+                                                      int64_t chunk_start) {
+  if (!overwrite && *n_scored - chunk_start <= 0) return;   // the GEMM launch left dW (and part) alone
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int t = (int)(q / (BM * BN)), within = (int)(q % (BM * BN));
+  if (t >= tiles) return;
+  const int v = (tail_m0 + t / Nt) * BM + within / BN, n = (t % Nt) * BN + within % BN;
+  if (v >= V || n >= d) return;
+  float s = 0.f;
+  for (int k = 0; k < split; ++k) s += part[((int64_t)k * tiles + t) * (BM * BN) + within];
+  float* out = dW + (int64_t)v * d + n;
+  *out = overwrite ? s : *out + s;
 }
 
 template <int MODE>
@@ -566,8 +638,21 @@ void launch(Params& p, hipStream_t stream) {
   const int Mt = (p.M + BM - 1) / BM, Nt = (p.N + BN - 1) / BN;
   const SuperTile st = pick_super_tile(Nt);
   p.sup_m = st.m; p.sup_n = st.n;
-  const int blocks = num_blocks(Mt, Nt, st.m, st.n);
+  int blocks = num_blocks(Mt, Nt, st.m, st.n);
+  DwTailPlan tail = {0, 0, 0};
+  if (MODE == MODE_DW && p.tail_part != nullptr) tail = dw_tail_plan(Mt, Nt, st.m);
+  if (tail.split > 0) {
+    const int items = tail.rows * Nt * tail.split;
+    p.main_blocks = num_blocks(tail.m0, Nt, st.m, st.n);
+    p.tail_m0 = tail.m0; p.tail_rows = tail.rows; p.tail_split = tail.split;
+    blocks = p.main_blocks + (items + NXCD - 1) / NXCD * NXCD;
+  }
   hipLaunchKernelGGL(gemm_nt_bf16<MODE>, dim3(blocks), dim3(NTHREADS), lds_bytes<MODE>(), stream, p);
+  if (tail.split > 0) {
+    const int tiles = tail.rows * Nt;
+    hipLaunchKernelGGL(dw_tail_reduce, dim3(tiles * (BM * BN / 256)), dim3(256), 0, stream, p.tail_part, tiles,
+                       tail.split, Nt, tail.m0, p.V, p.d, p.dW, p.overwrite, p.n_scored, p.chunk_start);
+  }
 }
 
 }  // namespace
@@ -602,15 +687,18 @@ void launch_gemm_dh_bf16(const void* E, int64_t lde, const void* Wt, int64_t ldw
   launch<MODE_DH>(p, stream);
 }
 
+size_t gemm_dw_tail_bytes() { return (size_t)kDwTailMaxItems * BM * BN * sizeof(float); }
+
 void launch_gemm_dw_bf16(const void* E, int64_t lde, const void* Ht, int64_t ldht,
                          const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                         int V, int d, float* dW, int overwrite, hipStream_t stream) {
+                         int V, int d, float* dW, int overwrite, float* tail_part, hipStream_t stream) {
   Params p = {};
   p.A = static_cast<const uint16_t*>(E); p.lda = lde; p.M = (int)round_up(V, kTile);
   p.B = static_cast<const uint16_t*>(Ht); p.ldb = ldht; p.N = d;
   p.K = chunk_rows;
   p.n_scored = n_scored; p.chunk_start = chunk_start; p.chunk_rows = chunk_rows;
   p.dW = dW; p.overwrite = overwrite; p.V = V; p.d = d;
+  p.tail_part = tail_part;
   launch<MODE_DW>(p, stream);
 }
 

@@ -74,9 +74,12 @@ void launch_gemm_dh_bf16(const void* E, int64_t lde, const void* Wt, int64_t ldw
 // columns >= V must be zero), B = Ht [d, chunk_rows] (the pass's hidden rows, each already
 // multiplied by its row scale); dW[v, :] = (or +=) sum over the chunk's valid rows.
 // overwrite = 1 stores, 0 adds into the existing values.
+// tail_part: scratch of gemm_dw_tail_bytes() bytes for the K-split tail tiles (nullptr: the
+// ragged last rows of tiles run as whole tiles).
+size_t gemm_dw_tail_bytes();
 void launch_gemm_dw_bf16(const void* P, int64_t ldp, const void* Ht, int64_t ldht,
                          const int64_t* n_scored, int64_t chunk_start, int chunk_rows,
-                         int V, int d, float* dW, int overwrite, hipStream_t stream);
+                         int V, int d, float* dW, int overwrite, float* tail_part, hipStream_t stream);
 
 // ---- fp32 plain GEMM (sanity path): C[m][n] = sum_k A[m][k] * B[n][k] --------
 // a_rows / c_rows: optional row maps (index arrays already offset to the chunk);

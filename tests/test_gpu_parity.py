@@ -148,7 +148,7 @@ def test_single_chunk_default_and_fp32_dh(mrl, synth):
 
 
 def test_peaked_softmax(mrl, synth):
-    # hidden states scaled x8: logits of std ~ 6, exercises the max-subtraction and fp16 stash
+    # hidden states scaled x8: logits of std ~ 6, exercises the range of the stashed exponentials
     sp = synth.spec(2, n_prompts=2, T=24, V=3000, d=256)
     _run_both(mrl, synth, sp, chunk_rows=256, h_scale=8.0)
 
