@@ -68,6 +68,7 @@ template <int MODE> constexpr int lds_bytes() {
 constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
+template <bool B> struct Flag { static constexpr bool value = B; };
 
 struct Params {
   const uint16_t* A; int64_t lda; int M;
@@ -151,6 +152,18 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  // Lane and wave number as the code after the K loop takes them: recomputed there from the
+  // execution mask and a scalar, so that nothing lane-dependent has to stay alive (that is, be
+  // spilled to scratch memory) across the loop, whose body owns every vector register.  A
+  // reload from scratch is a vector-memory load: the wait for it would also wait for every
+  // store issued before it, and between the stores of the forward epilogue that costs
+  // microseconds each time.
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto lane_now = []() {
+    int l = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(l));   // opaque: what is derived from it is computed where it is used, not hoisted
+    return l;
+  };
 
   // valid rows of this chunk (device-side, no host sync)
   int64_t nv64 = *p.n_scored - p.chunk_start;
@@ -455,6 +468,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   const int ncol_base = n0 + wn * 128 + frow;
 
   if (MODE == MODE_FWD) {
+    const int lane = lane_now(), wave = wave_u;
+    const int wm = wave >> 1, wn = wave & 1, frow = lane & 15, fq = lane >> 4;
+    const int ncol_base = n0 + wn * 128 + frow;
     // rows = vocabulary ids, cols = token rows of the chunk.  Exponentials are taken relative to
     // the row's offset c2 = z_target * log2(e) + margin (log2 domain), one offset for all
     // vocabulary tiles of a row: e = 2^(z log2(e) - c2), clamped so that neither e nor any sum of
@@ -467,49 +483,66 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     auto vrow = [&](int i, int e) {
       return m0 + wm * 128 + 32 * (i >> 1) + 8 * fq + 4 * (i & 1) + e;
     };
-    const bool want_ez = p.part_ez != nullptr;
+    // The body is instantiated for full / ragged vocabulary tiles and with / without the entropy
+    // sums: both conditions are uniform, and left as run-time selects they cost four more
+    // instructions per logit (row id, compare, two selects) than the six the work needs
+    // (accumulator read, multiply-add, clamp, exponential, add, half a packed conversion).
+    auto body = [&](auto full_tile, auto with_ez) {
+      constexpr bool kFull = decltype(full_tile)::value, kEz = decltype(with_ez)::value;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int n = ncol_base + j * 16;
-      const bool live = n < N;
-      const float zt = *reinterpret_cast<const float*>(smem + PIPE_BYTES + (wn * 128 + frow + j * 16) * 4);
-      const float c2 = live ? fmaf(zt, LOG2E, kStashMargin2) : 0.f;
-      uint16_t* erow = p.estash + (int64_t)n * p.lde + m0 + wm * 128 + 8 * fq;
-      float s = 0.f, t = 0.f;
+      for (int j = 0; j < 8; ++j) {
+        const int n = ncol_base + j * 16;
+        const bool live = n < N;
+        const float zt = *reinterpret_cast<const float*>(smem + PIPE_BYTES + (wn * 128 + frow + j * 16) * 4);
+        const float c2 = live ? fmaf(zt, LOG2E, kStashMargin2) : 0.f;
+        uint16_t* erow = p.estash + (int64_t)n * p.lde + m0 + wm * 128 + 8 * fq;
+        float s = 0.f, t = 0.f;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        // accumulators 2q and 2q+1 hold 8 consecutive vocabulary ids of this lane
-        bf16x8 h;
+        for (int q = 0; q < 4; ++q) {
+          // accumulators 2q and 2q+1 hold 8 consecutive vocabulary ids of this lane
+          bf16x8 h;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+          for (int u = 0; u < 2; ++u)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float z = acc[2 * q + u][j][e];
-            float w = exp2_fast(fminf(fmaf(z, LOG2E, -c2), kStashClamp2));
-            if (!full) w = vrow(2 * q + u, e) < p.V ? w : 0.f;
-            s += w;
-            if (want_ez) t = fmaf(w, z, t);     // for the entropy: sum e * z  (H = lse - E_p[z])
-            h[4 * u + e] = (__bf16)w;
+            for (int e = 0; e < 4; ++e) {
+              // (read where it is used: left to the compiler, the copies out of the accumulation
+              // registers are hoisted to the top of the epilogue and fill the register file)
+              float z;
+              asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(z) : "a"(acc[2 * q + u][j][e]));
+              float w = exp2_fast(fminf(fmaf(z, LOG2E, -c2), kStashClamp2));
+              if (!kFull) w = vrow(2 * q + u, e) < p.V ? w : 0.f;
+              s += w;
+              if (kEz) t = fmaf(w, z, t);     // for the entropy: sum e * z  (H = lse - E_p[z])
+              h[4 * u + e] = (__bf16)w;
+            }
+          if (p.estash != nullptr && live) {
+            // 16 bytes per lane, the four lanes of a token row side by side (64 bytes).  Streaming
+            // store (non-temporal, device scope): the stash is 5 GB per launch and is next read by
+            // the backward launches, so it should not displace operand panels from the L2 and the
+            // memory-side cache (2 % of the launch against a plain store).  Written in assembly
+            // for its cache policy bits; the two wait states after it are the ones the hardware
+            // needs before the data registers of a store wider than 8 bytes may be overwritten
+            // (the compiler inserts them for its own stores only).
+            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" :: "v"(erow + 32 * q), "v"(h) : "memory");
           }
-        if (p.estash != nullptr && live) {
-          // 16 bytes per lane, the four lanes of a token row side by side (64 bytes).  Streaming
-          // store (non-temporal, device scope): the stash is 5 GB per launch and is next read by
-          // the backward launches, so it should not displace operand panels from the L2 and the
-          // memory-side cache (2 % of the launch against a plain store).  Written in assembly
-          // for its cache policy bits; the two wait states after it are the ones the hardware
-          // needs before the data registers of a store wider than 8 bytes may be overwritten
-          // (the compiler inserts them for its own stores only).
-          asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" :: "v"(erow + 32 * q), "v"(h) : "memory");
         }
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (fq == 0 && live) p.part_sum[(int64_t)pidx * p.part_stride + n] = s;
+        if (kEz) {
+          t += __shfl_xor(t, 16);
+          t += __shfl_xor(t, 32);
+          if (fq == 0 && live) p.part_ez[(int64_t)pidx * p.part_stride + n] = t;
+        }
+        // one column block at a time: interleaving them runs the register allocator out of
+        // registers, and its reloads from scratch wait for the stores issued so far
+        __builtin_amdgcn_sched_barrier(0);
       }
-      s += __shfl_xor(s, 16);
-      s += __shfl_xor(s, 32);
-      if (fq == 0 && live) p.part_sum[(int64_t)pidx * p.part_stride + n] = s;
-      if (want_ez) {
-        t += __shfl_xor(t, 16);
-        t += __shfl_xor(t, 32);
-        if (fq == 0 && live) p.part_ez[(int64_t)pidx * p.part_stride + n] = t;
-      }
+    };
+    if (full) {
+      if (p.part_ez != nullptr) body(Flag<true>{}, Flag<true>{}); else body(Flag<true>{}, Flag<false>{});
+    } else {
+      if (p.part_ez != nullptr) body(Flag<false>{}, Flag<true>{}); else body(Flag<false>{}, Flag<false>{});
     }
   } else if (MODE == MODE_DH) {
     // rows = token rows of the chunk (scattered to their slots), cols = hidden index; a row
