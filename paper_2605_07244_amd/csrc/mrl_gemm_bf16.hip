@@ -68,6 +68,7 @@ template <int MODE> constexpr int lds_bytes() {
 constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DW = 2 };
+constexpr int NXCD = 8;
 template <bool B> struct Flag { static constexpr bool value = B; };
 
 struct Params {
@@ -87,6 +88,7 @@ struct Params {
   // tile rows tail_m0 .. tail_m0 + tail_rows - 1, each cut into tail_split slices of the
   // contraction, and store their accumulators to tail_part instead of dW
   int main_blocks, tail_m0, tail_rows, tail_split; float* tail_part;
+  int tail_first[NXCD + 1];   // items tail_first[x] .. tail_first[x + 1] - 1 run on XCD x
 };
 
 // Workgroup -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs, each with its own
@@ -99,7 +101,6 @@ struct Params {
 // with a half-empty last column: dH / dW 11-30 % slower than 8 x 2), and the super-tile size
 // must divide the 32 compute units of an XCD, so that the workgroups running on it at any time
 // are whole super-tiles (shapes of 24, 28 or 30 tiles lose 5-20 %).
-constexpr int NXCD = 8;
 struct SuperTile { int m, n; };
 inline SuperTile pick_super_tile(int Nt) {
   if (Nt % 4 == 0) return {8, 4};
@@ -185,13 +186,13 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
     if ((int)blockIdx.x < p.main_blocks) {
       if (!tile_coords(blockIdx.x, p.tail_m0, Nt, p.sup_m, p.sup_n, tm, tn, sm, sn)) return;
     } else {
-      // one XCD takes consecutive items, i.e. (when the counts divide) all tiles of one slice:
-      // they walk the same K range and share its operand panels in that L2
+      // one XCD takes consecutive items (the host says how many: the XCDs that the whole tiles
+      // leave idle earlier take more), i.e. mostly tiles of one slice: they walk the same K range
+      // and share its operand panels in that L2
       const int e = blockIdx.x - p.main_blocks;
-      const int tiles = p.tail_rows * Nt, items = tiles * p.tail_split;
-      const int per_xcd = (items + NXCD - 1) / NXCD;
-      const int item = (e % NXCD) * per_xcd + e / NXCD;
-      if (e / NXCD >= per_xcd || item >= items) return;
+      const int tiles = p.tail_rows * Nt;
+      const int item = p.tail_first[e % NXCD] + e / NXCD;
+      if (item >= p.tail_first[e % NXCD + 1]) return;
       const int slice = item / tiles, t = item % tiles;
       sm = t / Nt; sn = t % Nt;
       tm = p.tail_m0 + sm; tn = sn;
@@ -633,19 +634,61 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
 // dW tail.  The workgroup -> tile mapping runs whole super-tile rows of sup_m tile rows; V / 256
 // tile rows leave a last, ragged super-tile row (2 tile rows x 16 tiles at V = 151936, d = 4096)
 // that keeps an eighth of the compute units busy for the time of a full tile while the others
-// idle: 2.3 % of the launch.  Those tiles are cut into up to 8 slices of the contraction (the
-// pass's token rows) so that the tail is as many work items as there are compute units, each an
-// eighth as long.  The slices store their accumulators to a scratch area and dw_tail_reduce
-// adds them, slice 0 first, into dW: the result does not depend on execution order.
-struct DwTailPlan { int m0, rows, split; };
-inline DwTailPlan dw_tail_plan(int Mt, int Nt, int sup_m) {
-  DwTailPlan t = {Mt / sup_m * sup_m, Mt % sup_m, 0};
-  const int tiles = t.rows * Nt;
-  if (tiles > 0 && t.m0 > 0) {
-    const int s = kDwTailMaxItems / tiles;
-    t.split = s >= 8 ? 8 : (s >= 2 ? s : 0);
+// idle: 2.3 % of the launch.  Those tiles can be cut into up to 8 slices of the contraction (the
+// pass's token rows), work items a fraction of a tile long that fill the compute units the whole
+// tiles leave idle at the end.  The slices store their accumulators to a scratch area and
+// dw_tail_reduce adds them, slice 0 first, into dW: the result does not depend on execution order.
+// Workgroup b runs on XCD b % 8 whatever else is free, so the plan is made per XCD: a model of
+// the launch (32 compute units per XCD, whole tiles in id order, then the items) gives the time
+// the last item ends for every split and for the unsplit mapping; the best one is taken, and the
+// items are dealt to the XCDs as the model placed them.  (Host code that runs once per launch in
+// microseconds: not optimised, the optimiser takes very long over its nested constant loops.)
+struct DwTailPlan { int m0, rows, split, first[NXCD + 1]; };
+__attribute__((optnone, noinline)) DwTailPlan dw_tail_plan(int Mt, int Nt, int sup_m, int sup_n) {
+  constexpr int kCus = 32;                       // per XCD
+  constexpr double kItemOverhead = 0.02;         // prologue, partial-tile store, reduce: in tile times
+  DwTailPlan best = {Mt / sup_m * sup_m, Mt % sup_m, 0, {}};
+  const int tiles = best.rows * Nt;
+  if (tiles == 0 || best.m0 == 0) return best;
+  const int sNt = (Nt + sup_n - 1) / sup_n;
+  // tiles per XCD of the first `rows_m` tile rows under the super-tile mapping
+  auto tiles_per_xcd = [&](int rows_m, int (&t)[NXCD]) {
+    for (int x = 0; x < NXCD; ++x) t[x] = 0;
+    const int sMt = (rows_m + sup_m - 1) / sup_m;
+    for (int s = 0; s < sMt * sNt; ++s) {
+      const int rm = rows_m - (s / sNt) * sup_m, rn = Nt - (s % sNt) * sup_n;
+      t[s % NXCD] += (rm < sup_m ? rm : sup_m) * (rn < sup_n ? rn : sup_n);
+    }
+  };
+  int t_all[NXCD], t_main[NXCD];
+  tiles_per_xcd(Mt, t_all);
+  tiles_per_xcd(best.m0, t_main);
+  double unsplit = 0;
+  for (int x = 0; x < NXCD; ++x) { const double e = (t_all[x] + kCus - 1) / kCus; unsplit = e > unsplit ? e : unsplit; }
+  double best_end = unsplit - kItemOverhead;     // a split has to beat the plain mapping by a margin
+  for (int split = 2; split <= 8 && tiles * split <= kDwTailMaxItems; ++split) {
+    // free[x][c]: when compute unit c of XCD x has finished its whole tiles
+    double free_at[NXCD][kCus];
+    for (int x = 0; x < NXCD; ++x)
+      for (int c = 0; c < kCus; ++c) free_at[x][c] = t_main[x] / kCus + (c < t_main[x] % kCus ? 1 : 0);
+    int count[NXCD] = {};
+    double end = 0;
+    for (int x = 0; x < NXCD; ++x) for (int c = 0; c < kCus; ++c) end = free_at[x][c] > end ? free_at[x][c] : end;
+    for (int i = 0; i < tiles * split; ++i) {
+      int bx = 0, bc = 0;
+      for (int x = 0; x < NXCD; ++x)
+        for (int c = 0; c < kCus; ++c)
+          if (free_at[x][c] < free_at[bx][bc]) { bx = x; bc = c; }
+      free_at[bx][bc] += 1.0 / split + kItemOverhead;
+      end = free_at[bx][bc] > end ? free_at[bx][bc] : end;
+      count[bx]++;
+    }
+    if (end < best_end - 1e-9) {
+      best_end = end; best.split = split; best.first[0] = 0;
+      for (int x = 0; x < NXCD; ++x) best.first[x + 1] = best.first[x] + count[x];
+    }
   }
-  return t;
+  return best;
 }
 
 __global__ __launch_bounds__(256) void dw_tail_reduce(const float* __restrict__ part, int tiles, int split, int Nt,
@@ -672,13 +715,18 @@ void launch(Params& p, hipStream_t stream) {
   const SuperTile st = pick_super_tile(Nt);
   p.sup_m = st.m; p.sup_n = st.n;
   int blocks = num_blocks(Mt, Nt, st.m, st.n);
-  DwTailPlan tail = {0, 0, 0};
-  if (MODE == MODE_DW && p.tail_part != nullptr) tail = dw_tail_plan(Mt, Nt, st.m);
+  DwTailPlan tail = {0, 0, 0, {}};
+  if (MODE == MODE_DW && p.tail_part != nullptr) tail = dw_tail_plan(Mt, Nt, st.m, st.n);
   if (tail.split > 0) {
-    const int items = tail.rows * Nt * tail.split;
     p.main_blocks = num_blocks(tail.m0, Nt, st.m, st.n);
     p.tail_m0 = tail.m0; p.tail_rows = tail.rows; p.tail_split = tail.split;
-    blocks = p.main_blocks + (items + NXCD - 1) / NXCD * NXCD;
+    int most = 0;
+    for (int x = 0; x < NXCD; ++x) {
+      p.tail_first[x] = tail.first[x];
+      most = tail.first[x + 1] - tail.first[x] > most ? tail.first[x + 1] - tail.first[x] : most;
+    }
+    p.tail_first[NXCD] = tail.first[NXCD];
+    blocks = p.main_blocks + most * NXCD;
   }
   hipLaunchKernelGGL(gemm_nt_bf16<MODE>, dim3(blocks), dim3(NTHREADS), lds_bytes<MODE>(), stream, p);
   if (tail.split > 0) {

@@ -142,6 +142,13 @@ def test_mini_config5_full_vocab_and_width(mrl, synth):
     _run_both(mrl, synth, sp, chunk_rows=256)
 
 
+def test_mini_config2_full_vocab_uneven_dw_tail(mrl, synth):
+    # full V = 151936 at d = 1536: the last two rows of dW tiles (12 tiles) are cut into K slices that
+    # the launch plan deals to the XCDs unevenly (those that finish their whole tiles early take them)
+    sp = synth.spec(2, n_prompts=1, T=40)
+    _run_both(mrl, synth, sp, chunk_rows=256)
+
+
 def test_single_chunk_default_and_fp32_dh(mrl, synth):
     sp = synth.spec(2, n_prompts=2, T=40, V=2500)
     _run_both(mrl, synth, sp, chunk_rows=0, dh_dtype=0)
