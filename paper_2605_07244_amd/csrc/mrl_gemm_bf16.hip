@@ -220,7 +220,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_nt_bf16(Params p) {
   // FWD: the 16 rows of A fragment i are not 16 consecutive panel rows but
   //   rho(i, r) = 32*(i/2) + 8*(r/4) + 4*(i%2) + r%4      (within the wave's 128 rows),
   // so that a lane's accumulators (i = 2t, 2t+1; e = 0..3) are 8 consecutive vocabulary ids
-  // and the fp16 stash can be stored from registers, 16 bytes per lane, without an LDS round
+  // and the bf16 stash of exponentials can be stored from registers, 16 bytes per lane, without an LDS round
   // trip.  The chunk swizzle of the A panel then takes row bits 1, 3, 4 (the ones that vary
   // inside a fragment) instead of bits 1-3.
   constexpr bool A_PERM = (MODE == MODE_FWD);

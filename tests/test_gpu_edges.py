@@ -149,6 +149,20 @@ def test_runs_are_bit_reproducible(mrl, synth):
     assert a["st"] == c["st"]
 
 
+def test_dw_with_k_split_tail_is_bit_reproducible_and_accumulates(mrl, synth):
+    # V = 151936, d = 1536: the ragged last rows of dW tiles are cut into K slices whose partial tiles a
+    # second kernel adds in slice order; two passes, so that the second adds into the first's result
+    sp, b = _small(synth, n_prompts=2, T=48, V=151936, d=1536)
+    a = _gpu_loss(mrl, sp, b)
+    c = _gpu_loss(mrl, sp, b)
+    assert int(b["mask"].sum()) > 256 and torch.equal(a["dW"], c["dW"]) and torch.equal(a["dH"], c["dH"])
+    one = _gpu_loss(mrl, sp, b, cfg=dict(chunk_rows=512))          # one pass
+    scale = float(one["dW"].abs().max())
+    assert float((a["dW"] - one["dW"]).abs().max()) <= 1e-5 * scale   # fp32 sums in a different order
+    tail = a["dW"][151936 // 256 // 8 * 8 * 256:]                     # the rows of the split tiles
+    assert float(tail.abs().max()) > 0
+
+
 def test_kl_off_without_reference(mrl, synth):
     sp, b = _small(synth)
     lc = mrl.LossConfig(kl_beta=0.0, chunk_rows=256)
