@@ -54,6 +54,18 @@ int mrl_profile_collect(double* ms_per_class /*host*/, int64_t* launches_per_cla
 int mrl_probe_mfma_rate(int32_t random_operands, double seconds, void* scratch /*dev*/,
                         size_t scratch_bytes, double* out_tflops /*host*/);
 
+/* ------------------------------------------------------------------------
+ * The launch plan of the dW GEMM for an LM head of V rows and d columns (host
+ * code only, no GPU call): which rows of 256 x 256 tiles are cut into slices of
+ * the contraction at the end of the launch, into how many, and how many of the
+ * resulting work items each of the 8 XCDs takes.  For tests of the host logic
+ * and for reading profiles.  out12 (host): [0] first tile row of the tail,
+ * [1] tile rows in the tail, [2] slices per tile (0: the tiles stay whole),
+ * [3 + x], x = 0..8: items before XCD x (so [11] is the item count).
+ * Errors: MRL_ERR_NULL, MRL_ERR_SHAPE (V or d not positive).
+ * ---------------------------------------------------------------------- */
+int mrl_diag_dw_tail_plan(int32_t V, int32_t d, int32_t* out12 /*host*/);
+
 #ifdef __cplusplus
 }
 #endif

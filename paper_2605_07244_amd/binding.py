@@ -109,6 +109,8 @@ def lib() -> ctypes.CDLL:
     L.mrl_thl_word_align.restype = c_int
     L.mrl_thl_word_align.argtypes = [c_void_p] * 7 + [c_int64, c_int32, c_int32, c_int32, c_float, c_void_p,
                                                       c_void_p, c_void_p]
+    L.mrl_diag_dw_tail_plan.restype = c_int
+    L.mrl_diag_dw_tail_plan.argtypes = [c_int32, c_int32, POINTER(c_int32)]
     L.mrl_probe_mfma_rate.restype = c_int
     L.mrl_probe_mfma_rate.argtypes = [c_int32, c_double, c_void_p, c_size_t, POINTER(c_double)]
     _LIB = L
@@ -294,6 +296,13 @@ def profile_collect() -> dict:
     n = (c_int64 * len(PROF_CLASSES))()
     _check(lib().mrl_profile_collect(ms, n), "mrl_profile_collect")
     return {name: (ms[i], n[i]) for i, name in enumerate(PROF_CLASSES)}
+
+
+def dw_tail_plan(V: int, d: int) -> dict:
+    """Launch plan of the dW GEMM's K-split tail for a [V, d] head (host code only)."""
+    out = (c_int32 * 12)()
+    _check(lib().mrl_diag_dw_tail_plan(int(V), int(d), out), "mrl_diag_dw_tail_plan")
+    return dict(first_tile_row=out[0], tile_rows=out[1], split=out[2], items_before_xcd=list(out[3:12]))
 
 
 def probe_mfma_rate(random_operands: bool, seconds: float = 0.5, device="cuda:0") -> float:

@@ -29,6 +29,8 @@
 //        row scale (-g / S) and scattered to its slot.
 //   DW : A = stash^T, read from the stash rows themselves (K-major panel, transposing
 //        LDS reads), B = (row-scaled H)^T; fp32 read-modify-write of dW.
+#include "../../include/mrl.h"
+#include "../../include/mrl_diag.h"
 #include "mrl_internal.h"
 
 namespace mrl {
@@ -784,3 +786,15 @@ void launch_gemm_dw_bf16(const void* E, int64_t lde, const void* Ht, int64_t ldh
 }
 
 }  // namespace mrl
+
+extern "C" int mrl_diag_dw_tail_plan(int32_t V, int32_t d, int32_t* out12) {
+  using namespace mrl;
+  if (out12 == nullptr) return MRL_ERR_NULL;
+  if (V <= 0 || d <= 0) return MRL_ERR_SHAPE;
+  const int Mt = (int)(round_up(V, kTile) / BM), Nt = (d + BN - 1) / BN;
+  const SuperTile st = pick_super_tile(Nt);
+  const DwTailPlan t = dw_tail_plan(Mt, Nt, st.m, st.n);
+  out12[0] = t.m0; out12[1] = t.rows; out12[2] = t.split;
+  for (int x = 0; x <= NXCD; ++x) out12[3 + x] = t.split > 0 ? t.first[x] : 0;
+  return MRL_OK;
+}

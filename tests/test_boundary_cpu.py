@@ -148,6 +148,35 @@ def test_probe_argument_errors():
     assert f(0, 60.0, FAKE, 1 << 20, ctypes.byref(out)) == -7
 
 
+def test_dw_tail_plan_host_logic():
+    """The plan of the dW launch's K-split tail: every item of every split tile is dealt to exactly one XCD,
+    the partial-tile scratch (256 tiles) is never exceeded, whole super-tile rows are left alone."""
+    f = m.lib().mrl_diag_dw_tail_plan
+    out = (ctypes.c_int32 * 12)()
+    assert f(1000, 64, None) == -1 and f(0, 64, out) == -2 and f(1000, 0, out) == -2
+    seen_split = set()
+    for V in (300, 2048, 2500, 3001, 8333, 32000, 50257, 128256, 151936, 262144):
+        for d in (64, 384, 768, 1536, 2048, 3584, 4096, 5120, 8192):
+            assert f(V, d, out) == 0
+            m0, rows, split = out[0], out[1], out[2]
+            pre = list(out[3:12])
+            Mt, Nt = -(-V // 256), -(-d // 256)
+            sup_m = 16 if Nt == 1 else 8
+            assert m0 % sup_m == 0 and m0 + rows == Mt and 0 <= rows < sup_m
+            assert split == 0 or 2 <= split <= 8
+            if split:
+                items = rows * Nt * split
+                assert m0 > 0 and rows > 0 and items <= 256
+                assert pre[0] == 0 and pre[8] == items and all(a <= b for a, b in zip(pre, pre[1:]))
+            else:
+                assert pre == [0] * 9
+            seen_split.add(split)
+    assert 0 in seen_split and 8 in seen_split and len(seen_split) >= 3
+    # the benchmark shapes: V = 151936 leaves two ragged tile rows
+    assert f(151936, 4096, out) == 0 and (out[0], out[1], out[2]) == (592, 2, 8) and list(out[3:12]) == list(range(0, 257, 32))
+    assert f(151936, 1536, out) == 0 and out[2] >= 2 and out[11] == 12 * out[2]
+
+
 def test_thl_word_align_argument_errors():
     f = m.lib().mrl_thl_word_align
     args = lambda **kw: [kw.get("p0", FAKE), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, kw.get("B", 4), kw.get("S", 16), 16,
