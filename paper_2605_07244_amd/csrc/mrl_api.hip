@@ -16,7 +16,7 @@ static __device__ __align__(256) unsigned char scratch[MRL_STATIC_SCRATCH_BYTES]
 namespace mrl {
 namespace {
 
-constexpr int kDefaultChunkBf16 = 32768;   // rows per pass: amortises the fp32 dW read-modify-write
+constexpr int kDefaultChunkBf16 = 65536;   // rows per pass: amortises the fp32 dW read-modify-write (20 GB of stash at V = 151936)
 constexpr int kFwdSubChunk = 16384;        // forward launches cover this many rows: their H rows stay in the Infinity Cache
 constexpr int kDefaultChunkF32 = 2048;
 constexpr int64_t kMaxSlots = (int64_t)1 << 30;

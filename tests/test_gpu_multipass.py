@@ -1,7 +1,7 @@
 """Parity in the launch configuration the benchmark times, with every output compared
 element by element.
 
-The default chunking (passes of 32768 scored rows, forward launches of 16384 rows, fp32
+The default chunking (passes of 65536 scored rows, forward launches of 16384 rows, fp32
 read-modify-write of dW from the second pass on) is run over three passes with a ragged last
 pass and a ragged last vocabulary tile, at a size the fp64 oracle computes in full: the oracle
 functions are called on row chunks here in the test (its logits matrix for all rows at once would
@@ -48,12 +48,12 @@ def _oracle_chunked(b, seq_adv, cfg, eps):
 def case():
     import paper_2605_07244_amd as mrl
     from workloads import synth
-    # 14 prompts x 8 rollouts x 1024 slots, lengths uniform in [256, 1024]: about 72 k scored rows =
-    # two full passes of 32768 and a ragged third; V = 32 full 256-wide tiles and a ragged one of 141
-    sp = synth.spec(2, n_prompts=14, T=1024, V=8333, d=384)
+    # 28 prompts x 8 rollouts x 1024 slots, lengths uniform in [256, 1024]: about 143 k scored rows =
+    # two full passes of 65536 and a ragged third; V = 32 full 256-wide tiles and a ragged one of 141
+    sp = synth.spec(2, n_prompts=28, T=1024, V=8333, d=384)
     b = synth.make(sp, "cuda")
     n_scored = int(b["mask"].sum())
-    assert 2 * 32768 < n_scored < 3 * 32768 and n_scored % 256 != 0 and b["V"] % 256 != 0
+    assert 2 * 65536 < n_scored < 3 * 65536 and n_scored % 256 != 0 and b["V"] % 256 != 0
     adv, _, _, _ = mrl.group_advantages(b["rewards_all"], b["group_all"], b["G"], b["in_stats"], b["scored"], b["is_own"])
     adv_o, *_ = util.oracle_advantages(b)
     assert np.allclose(adv.cpu().numpy(), adv_o, rtol=2e-6, atol=1e-7)
@@ -102,5 +102,5 @@ def test_default_chunking_three_passes_every_element(case, accumulate):
     util.check_gradient("dW", dW, want["dW"])
     # the ragged last vocabulary tile and the rows of the ragged last pass on their own
     util.check_gradient("dW[last tile]", dW[V // 256 * 256:], want["dW"][V // 256 * 256:])
-    last_pass = np.nonzero(m)[0][2 * 32768:]
+    last_pass = np.nonzero(m)[0][2 * 65536:]
     util.check_gradient("dH[last pass]", dH[last_pass], want["dH"][last_pass])
