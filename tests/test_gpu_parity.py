@@ -149,6 +149,18 @@ def test_mini_config2_full_vocab_uneven_dw_tail(mrl, synth):
     _run_both(mrl, synth, sp, chunk_rows=256)
 
 
+@pytest.mark.parametrize("V,d", [(8627, 2048), (20224, 2304), (7424, 2304), (11008, 1536), (16819, 640),
+                                 (13312, 2304), (17587, 1024)])
+def test_dw_tail_plans(mrl, synth, V, d):
+    """Head shapes whose dW launch cuts its ragged last rows of tiles into K slices, with 1 to 7 such rows,
+    2 to 8 slices, item counts that differ from XCD to XCD, and widths of a whole and of a ragged number of
+    256-wide tiles; two passes, so that the second adds the slices into the first's result."""
+    plan = mrl.dw_tail_plan(V, d)
+    assert plan["split"] >= 2
+    sp = synth.spec(2, n_prompts=2, T=40, V=V, d=d)
+    _run_both(mrl, synth, sp, chunk_rows=256)
+
+
 def test_single_chunk_default_and_fp32_dh(mrl, synth):
     sp = synth.spec(2, n_prompts=2, T=40, V=2500)
     _run_both(mrl, synth, sp, chunk_rows=0, dh_dtype=0)
